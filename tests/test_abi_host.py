@@ -1,0 +1,78 @@
+"""Host-side checks that need no GPU: the library loads, exports the declared C ABI, and validates arguments."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2403_12422_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "jetfire.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(jf_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = binding.load_library()
+    names = _declared_symbols()
+    assert len(names) >= 12
+    for name in names:
+        assert hasattr(lib, name), name
+    assert sorted(binding.EXPORTED_SYMBOLS) == names     # the binding covers the whole header, nothing more
+
+
+def test_error_strings_and_workspace():
+    lib = binding.load_library()
+    assert lib.jf_error_string(0) == b"JF_OK"
+    for code in range(1, 8):
+        assert lib.jf_error_string(code).startswith(b"JF_ERR_")
+    assert binding.jf_workspace_bytes(binding.JF_OP_LAYERNORM_BWD, 4096, 768, 0, 32) == 128 * 2 * 768 * 4
+    assert binding.jf_workspace_bytes(binding.JF_OP_LINEAR_FWD, 4096, 768, 3072, 32) == 0
+    assert binding.jf_workspace_bytes(binding.JF_OP_LAYERNORM_BWD, 4096, 768, 0, 48) == 0
+
+
+FAKE = ctypes.c_void_p(0x10000)        # aligned, never dereferenced: validation fails before any launch
+ODD = ctypes.c_void_p(0x10004)
+
+
+def test_argument_validation_returns_codes_without_launching():
+    lib = binding.load_library()
+    N, C, D = 64, 64, 64
+    lin = lambda **kw: lib.jf_linear_fwd(kw.get("X", FAKE), FAKE, FAKE, FAKE, kw.get("N", N), kw.get("C", C), D,
+                                         kw.get("block", 32), kw.get("Y", FAKE), kw.get("SY", FAKE), None, None, 0, None)
+    assert lin(X=None) == 1                                # JF_ERR_NULL
+    assert lin(Y=None) == 1
+    assert lin(N=0) == 2                                   # JF_ERR_SHAPE: empty
+    assert lin(N=48) == 2                                  # not a multiple of block
+    assert lin(C=(1 << 24) + 32) == 2                      # above the supported maximum
+    assert lin(block=48) == 3                              # JF_ERR_BLOCK
+    assert lin(X=ODD) == 4                                 # JF_ERR_ALIGN
+    # wgrad needs at least one output, and codes/scales come together
+    w = lambda dW, SdW, f: lib.jf_linear_wgrad(FAKE, FAKE, FAKE, FAKE, N, C, D, 32, dW, SdW, f, None, 0, None)
+    assert w(None, None, None) == 1
+    assert w(FAKE, None, None) == 1
+    # quantizer
+    qz = lambda **kw: lib.jf_quantize_block(kw.get("x", FAKE), kw.get("dt", 0), kw.get("rows", 64), 64, kw.get("ldx", 64),
+                                            32, FAKE, 64, FAKE, kw.get("qT", None), 64, kw.get("sT", None), None)
+    assert qz(x=None) == 1
+    assert qz(dt=5) == 7                                   # JF_ERR_DTYPE
+    assert qz(rows=33) == 2
+    assert qz(ldx=32) == 2
+    assert qz(qT=FAKE) == 1                                # qT without sT
+    # element-wise ops and the LayerNorm-backward workspace
+    assert lib.jf_gelu_q(FAKE, FAKE, 64, 65, 32, FAKE, FAKE, None) == 2
+    assert lib.jf_gelu_q_bwd(None, FAKE, FAKE, FAKE, 64, 64, 32, FAKE, FAKE, None) == 1
+    assert lib.jf_layernorm_q(FAKE, FAKE, None, FAKE, ctypes.c_float(1e-5), 64, 64, 32, FAKE, FAKE, FAKE, FAKE, None) == 1
+    assert lib.jf_layernorm_q_bwd(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 64, 64, 32, FAKE, FAKE, FAKE, FAKE, FAKE, 16, None) == 5
+    assert lib.jf_debug_linear_partials(0, FAKE, FAKE, 64, 64, 64, 32, 2, FAKE, None) == 2   # kb out of range
+    assert lib.jf_debug_linear_partials(3, FAKE, FAKE, 64, 64, 64, 32, 0, FAKE, None) == 2
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    with pytest.raises(binding.JetfireError):
+        binding.jf_quantize_block(torch.zeros(64, 64), 32)

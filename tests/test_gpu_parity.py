@@ -1,0 +1,254 @@
+"""GPU parity: every C-ABI entry point against the CPU oracle on the same seeded inputs (run with -m gpu).
+
+The GEMM / element-wise parity runs feed the ORACLE's INT8 operands to both sides so that errors do not compound;
+the quantizer's own parity is checked first.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2403_12422_amd as jf
+from paper_2403_12422_amd import workloads
+from parity import (assert_codes_close, assert_f32_close, assert_scales_close, block_amax, expand)
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def host(t):
+    return t.cpu().numpy()
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+# --------------------------------------------------------------------------- quantizer
+@pytest.mark.parametrize("block,rows,cols", [(32, 160, 352), (32, 256, 256), (64, 192, 320), (128, 256, 384), (32, 32, 32)])
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+def test_quantize_block(block, rows, cols, dtype):
+    say(f"quantize block={block} {rows}x{cols} {dtype}")
+    g = workloads.rng(1000 + block + rows)
+    x = workloads.gaussian(g, rows, cols, 1.0)
+    workloads.with_outlier_columns(g, x, 0.01, 20.0)
+    x[:block, :block] = 0.0                                   # an all-zero block
+    x[block // 2, cols - 3] = 5000.0                          # a single outlier
+    if dtype == "f16":
+        x = x.astype(np.float16).astype(np.float32)           # the oracle sees exactly what the kernel reads
+        xd = dev(x.astype(np.float16))
+    else:
+        xd = dev(x)
+    q, s, qT, sT = jf.jf_quantize_block(xd, block, transposed_copy=True)
+    torch.cuda.synchronize()
+    oq, os_ = oracle.quantize_block(x, block)
+    np.testing.assert_array_equal(host(s), os_)               # amax and its FP32 division are exact on both sides
+    assert_codes_close(host(q), oq, "codes", prequant=x, scales=os_, block=block)
+    np.testing.assert_array_equal(host(qT), host(q).T)
+    np.testing.assert_array_equal(host(sT), os_.T)
+    q2, s2 = jf.jf_quantize_block(xd, block)
+    np.testing.assert_array_equal(host(q2), host(q))
+    np.testing.assert_array_equal(host(s2), os_)
+
+
+# --------------------------------------------------------------------------- INT32 partial sums
+def _rand_codes(g, rows, cols):
+    return g.integers(-127, 128, size=(rows, cols)).astype(np.int8)
+
+
+@pytest.mark.parametrize("block,N,C,D", [(32, 256, 256, 256), (32, 160, 96, 224), (64, 192, 128, 320), (128, 256, 128, 384)])
+def test_int32_partials_bit_exact(block, N, C, D):
+    say(f"partials block={block} N={N} C={C} D={D}")
+    g = workloads.rng(2000 + block + N)
+    X, W, dY = _rand_codes(g, N, C), _rand_codes(g, D, C), _rand_codes(g, N, D)
+    X[:32, :32] = 127                                          # extreme sums +-B*127^2
+    W[:32, :32] = -127
+    Xd, Wd, dYd = dev(X), dev(W), dev(dY)
+    for kb in range(C // block):
+        got = host(jf.jf_debug_linear_partials(0, Xd, Wd, N, C, D, block, kb))
+        np.testing.assert_array_equal(got, oracle.block_partials(X, W, block, kb))
+    WT, XT, dYT = np.ascontiguousarray(W.T), np.ascontiguousarray(X.T), np.ascontiguousarray(dY.T)
+    for kb in range(D // block):
+        got = host(jf.jf_debug_linear_partials(1, dYd, Wd, N, C, D, block, kb))
+        np.testing.assert_array_equal(got, oracle.block_partials(dY, WT, block, kb))
+    for kb in range(N // block):
+        got = host(jf.jf_debug_linear_partials(2, dYd, Xd, N, C, D, block, kb))
+        np.testing.assert_array_equal(got, oracle.block_partials(dYT, XT, block, kb))
+
+
+# --------------------------------------------------------------------------- linear layer
+def _quantized_layer(seed, N, C, D, block, **kw):
+    X, W, dY = workloads.linear_layer(seed, N, C, D, **kw)
+    return oracle.quantize_block(X, block), oracle.quantize_block(W, block), oracle.quantize_block(dY, block)
+
+
+def _check_linear(name, got, want, block):
+    q, s, f = got
+    oq, os_, o32, o64 = want
+    f = host(f)
+    assert_f32_close(f, o64, block, name + " f32 vs float64 oracle")
+    exact = float(np.mean(f == o32))
+    say(f"  {name}: FP32 accumulator bit-identical to the oracle's FP32 accumulator on {100 * exact:.4f}% of elements")
+    assert exact == 1.0, name                                   # same fma order => same bits
+    assert_scales_close(host(s), os_, name + " scales")
+    nbad = assert_codes_close(host(q), oq, name + " codes", prequant=o32, scales=os_, block=block)
+    say(f"  {name}: {nbad} / {oq.size} codes differ by one (ties)")
+
+
+@pytest.mark.parametrize("block,N,C,D,kw", [
+    (32, 256, 256, 256, dict(w_std=1.0)),                       # config 1
+    (32, 160, 96, 224, {}),                                     # ragged against the 64/128 tiles, odd K steps
+    (32, 384, 160, 128, {}),
+    (64, 192, 128, 320, {}),
+    (128, 256, 128, 384, {}),
+    (128, 128, 384, 128, {}),
+])
+def test_linear_three_products(block, N, C, D, kw):
+    say(f"linear block={block} N={N} C={C} D={D}")
+    (X, SX), (W, SW), (dY, SdY) = _quantized_layer(3000 + block + N, N, C, D, block, **kw)
+    Xd, SXd, Wd, SWd, dYd, SdYd = map(dev, (X, SX, W, SW, dY, SdY))
+    _check_linear("fwd", jf.jf_linear_fwd(Xd, SXd, Wd, SWd, block, want_f32=True), oracle.linear_fwd(X, SX, W, SW, block), block)
+    _check_linear("dgrad", jf.jf_linear_dgrad(dYd, SdYd, Wd, SWd, block, want_f32=True), oracle.linear_dgrad(dY, SdY, W, SW, block), block)
+    _check_linear("wgrad", jf.jf_linear_wgrad(dYd, SdYd, Xd, SXd, block, want_f32=True), oracle.linear_wgrad(dY, SdY, X, SX, block), block)
+    # wgrad output variants: FP32 only, INT8 only
+    q0, s0, f0 = jf.jf_linear_wgrad(dYd, SdYd, Xd, SXd, block, want_q=False, want_f32=True)
+    assert q0 is None and s0 is None
+    q1, s1, f1 = jf.jf_linear_wgrad(dYd, SdYd, Xd, SXd, block, want_q=True, want_f32=False)
+    assert f1 is None
+    q2, s2, f2 = jf.jf_linear_wgrad(dYd, SdYd, Xd, SXd, block, want_f32=True)
+    np.testing.assert_array_equal(host(f0), host(f2))
+    np.testing.assert_array_equal(host(q1), host(q2))
+    np.testing.assert_array_equal(host(s1), host(s2))
+
+
+def test_linear_zero_blocks_and_run_to_run_stability():
+    block, N, C, D = 32, 128, 128, 128
+    (X, SX), (W, SW), _ = _quantized_layer(3100, N, C, D, block)
+    X[:32] = 0
+    SX[0] = 0.0                                                 # a whole row of all-zero input blocks -> zero output blocks
+    Xd, SXd, Wd, SWd = map(dev, (X, SX, W, SW))
+    q, s, f = jf.jf_linear_fwd(Xd, SXd, Wd, SWd, block, want_f32=True)
+    assert not host(q)[:32].any() and not host(s)[0].any() and not host(f)[:32].any()
+    assert np.all(np.isfinite(host(s)))
+    _check_linear("fwd(zero rows)", (q, s, f), oracle.linear_fwd(X, SX, W, SW, block), block)
+    q2, s2, f2 = jf.jf_linear_fwd(Xd, SXd, Wd, SWd, block, want_f32=True)
+    assert torch.equal(q, q2) and torch.equal(s, s2) and torch.equal(f, f2)
+
+
+def _sample_blocks(g, lm, ln, n):
+    n = min(n, lm * ln)
+    flat = g.choice(lm * ln, size=n, replace=False)
+    return flat // ln, flat % ln
+
+
+def _check_sampled(name, got, A, SA, Bm, SB, block, g, nblk=48):
+    """Full-size GPU result against the oracle on a sample of output blocks (each over the full K)."""
+    q, s, f = (host(t) for t in got)
+    M, Nn = q.shape
+    bp, bq = _sample_blocks(g, M // block, Nn // block, nblk)
+    oq, os_, o32, o64 = oracle.linear_nt_blocks(A, SA, Bm, SB, bp, bq, block)
+    nbad = 0
+    for n, (p, c) in enumerate(zip(bp, bq)):
+        sl = (slice(p * block, (p + 1) * block), slice(c * block, (c + 1) * block))
+        np.testing.assert_array_equal(f[sl], o32[n], err_msg=name)
+        assert_f32_close(f[sl], o64[n], block, name)
+        assert_scales_close(s[p, c], os_[n], name)
+        nbad += assert_codes_close(q[sl], oq[n], name, prequant=o32[n], scales=np.full((block, block), os_[n]))
+    assert nbad <= 1e-3 * len(bp) * block * block
+    # properties that hold everywhere: every non-zero block reaches +-127, scale = amax/127 of the FP32 output
+    amax = block_amax(f, block)
+    np.testing.assert_allclose(s, amax / np.float32(127), rtol=1e-6)
+    qa = block_amax(q.astype(np.float32), block)
+    assert np.all(qa[amax > 0] == 127)
+    err = np.abs(q.astype(np.float64) * expand(s.astype(np.float64), block) - f)
+    assert np.all(err <= 0.5 * expand(s.astype(np.float64), block) * (1 + 1e-5))
+    say(f"  {name}: {len(bp)} sampled blocks ok, {nbad} tie codes")
+
+
+def test_linear_config2_full_size_sampled():
+    """GPT-2-small MLP shape (tokens 4096, in 768, out 3072, block 32) in the launch configuration the benchmark times."""
+    block, N, C, D = 32, 4096, 768, 3072
+    say("linear config 2 full size")
+    (X, SX), (W, SW), (dY, SdY) = _quantized_layer(2, N, C, D, block)
+    Xd, SXd, Wd, SWd, dYd, SdYd = map(dev, (X, SX, W, SW, dY, SdY))
+    g = workloads.rng(4000)
+    _check_sampled("fwd", jf.jf_linear_fwd(Xd, SXd, Wd, SWd, block, want_f32=True), X, SX, W, SW, block, g)
+    WT, SWT = oracle.transpose(W, SW, block)
+    _check_sampled("dgrad", jf.jf_linear_dgrad(dYd, SdYd, Wd, SWd, block, want_f32=True), dY, SdY, WT, SWT, block, g)
+    dYT, SdYT = oracle.transpose(dY, SdY, block)
+    XT, SXT = oracle.transpose(X, SX, block)
+    _check_sampled("wgrad", jf.jf_linear_wgrad(dYd, SdYd, Xd, SXd, block, want_f32=True), dYT, SdYT, XT, SXT, block, g)
+
+
+@pytest.mark.parametrize("block", [64, 128])
+def test_linear_large_blocks_sampled(block):
+    N, C, D = 1024, 1024, 512
+    say(f"linear sampled block={block}")
+    X, W, dY = workloads.linear_layer(50 + block, N, C, D, act_std=1.0, w_std=1.0, grad_std=1.0,
+                                      outlier_fraction=0.005, outlier_factor=50.0)
+    (X, SX), (W, SW), (dY, SdY) = (oracle.quantize_block(a, block) for a in (X, W, dY))
+    Xd, SXd, Wd, SWd, dYd, SdYd = map(dev, (X, SX, W, SW, dY, SdY))
+    g = workloads.rng(4100 + block)
+    _check_sampled("fwd", jf.jf_linear_fwd(Xd, SXd, Wd, SWd, block, want_f32=True), X, SX, W, SW, block, g, 16)
+    WT, SWT = oracle.transpose(W, SW, block)
+    _check_sampled("dgrad", jf.jf_linear_dgrad(dYd, SdYd, Wd, SWd, block, want_f32=True), dY, SdY, WT, SWT, block, g, 16)
+    dYT, SdYT = oracle.transpose(dY, SdY, block)
+    XT, SXT = oracle.transpose(X, SX, block)
+    _check_sampled("wgrad", jf.jf_linear_wgrad(dYd, SdYd, Xd, SXd, block, want_f32=True), dYT, SdYT, XT, SXT, block, g, 16)
+
+
+# --------------------------------------------------------------------------- GELU
+def _check_eltwise(name, q, s, oq, os_, of64, block):
+    assert_scales_close(host(s), os_, name + " scales")
+    nbad = assert_codes_close(host(q), oq, name + " codes", prequant=of64, scales=os_, block=block)
+    say(f"  {name}: {nbad} / {oq.size} codes differ by one")
+
+
+@pytest.mark.parametrize("block,N,C", [(32, 96, 352), (64, 128, 192), (128, 256, 384), (32, 4096, 3072)])
+def test_gelu_fwd_bwd(block, N, C):
+    say(f"gelu block={block} {N}x{C}")
+    x, gr = workloads.gelu_case(5000 + block + N, N, C)
+    x[:block, :block] = 0.0
+    x[block:2 * block, :block] = -np.abs(x[block:2 * block, :block]) - 6.0     # a block deep in the negative tail
+    (X, SX), (G, SG) = oracle.quantize_block(x, block), oracle.quantize_block(gr, block)
+    Xd, SXd, Gd, SGd = map(dev, (X, SX, G, SG))
+    Y, SY = jf.jf_gelu_q(Xd, SXd, block)
+    oY, oSY, oy = oracle.gelu_q(X, SX, block)
+    _check_eltwise("gelu fwd", Y, SY, oY, oSY, oy, block)
+    dX, SdX = jf.jf_gelu_q_bwd(Gd, SGd, Xd, SXd, block)
+    odX, oSdX, odx = oracle.gelu_q_bwd(G, SG, X, SX, block)
+    _check_eltwise("gelu bwd", dX, SdX, odX, oSdX, odx, block)
+
+
+# --------------------------------------------------------------------------- LayerNorm
+@pytest.mark.parametrize("block,N,C", [(32, 96, 352), (32, 64, 1280), (64, 128, 192), (128, 256, 384), (32, 4096, 768)])
+def test_layernorm_fwd_bwd(block, N, C):
+    say(f"layernorm block={block} {N}x{C}")
+    x, gamma, beta, gr = workloads.layernorm_case(6000 + block + N, N, C)
+    x[0, :] = 3.0                                               # a constant row: variance 0
+    (X, SX), (G, SG) = oracle.quantize_block(x, block), oracle.quantize_block(gr, block)
+    Xd, SXd, Gd, SGd, gd, bd = map(dev, (X, SX, G, SG, gamma, beta))
+    eps = 1e-5
+    Y, SY, mean, rstd = jf.jf_layernorm_q(Xd, SXd, gd, bd, eps, block)
+    oY, oSY, omean, orstd, oy = oracle.layernorm_q(X, SX, gamma, beta, eps, block)
+    np.testing.assert_allclose(host(mean), omean, rtol=0, atol=1e-5 * np.abs(oracle.dequantize(X, SX, block)).max())
+    np.testing.assert_allclose(host(rstd), orstd, rtol=1e-5)
+    _check_eltwise("layernorm fwd", Y, SY, oY, oSY, oy, block)
+    # backward from the ORACLE's saved statistics, so that both sides start from identical inputs
+    dX, SdX, dgam, dbet = jf.jf_layernorm_q_bwd(Gd, SGd, Xd, SXd, gd, dev(omean), dev(orstd), block)
+    odX, oSdX, odg, odb, odx = oracle.layernorm_q_bwd(G, SG, X, SX, gamma, omean, orstd, block)
+    _check_eltwise("layernorm bwd", dX, SdX, odX, oSdX, odx, block)
+    gdq = oracle.dequantize(G, SG, block)
+    xh = (oracle.dequantize(X, SX, block) - omean[:, None].astype(np.float64)) * orstd[:, None].astype(np.float64)
+    # dgamma/dbeta: FP32 sums of N terms; tolerance relative to the sum of magnitudes
+    tol_g = 1e-5 * np.abs(gdq * xh).sum(axis=0) + 1e-30
+    tol_b = 1e-5 * np.abs(gdq).sum(axis=0) + 1e-30
+    assert np.all(np.abs(host(dgam).astype(np.float64) - odg) <= tol_g)
+    assert np.all(np.abs(host(dbet).astype(np.float64) - odb) <= tol_b)
+    # run-to-run bit stability of the column reductions
+    dX2, SdX2, dgam2, dbet2 = jf.jf_layernorm_q_bwd(Gd, SGd, Xd, SXd, gd, dev(omean), dev(orstd), block)
+    assert torch.equal(dgam, dgam2) and torch.equal(dbet, dbet2) and torch.equal(dX, dX2)

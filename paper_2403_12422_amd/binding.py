@@ -88,17 +88,25 @@ def jf_workspace_bytes(op, N, C, D, block):
     return int(load_library().jf_workspace_bytes(op, N, C, D, block))
 
 
-def jf_quantize_block(x, block=32, transposed_copy=False):
-    """x: (rows, cols) float32 or float16 CUDA tensor -> (q, s) or (q, s, qT, sT)."""
+def jf_quantize_block(x, block=32, transposed_copy=False, out=None):
+    """x: (rows, cols) float32 or float16 CUDA tensor -> (q, s) or (q, s, qT, sT).
+
+    `out` (here and in every function below) is an optional tuple of preallocated output tensors, in the
+    order they are returned; without it the outputs are allocated with torch."""
     lib = load_library()
     if x.dtype not in (torch.float32, torch.float16):
         raise JetfireError(7, "source must be float32 or float16")
     _dev(x, x.dtype, 2)
     rows, cols = x.shape
-    q = torch.empty((rows, cols), dtype=torch.int8, device=x.device)
-    s = torch.empty((max(rows // block, 0), max(cols // block, 0)), dtype=torch.float32, device=x.device)
     qT = sT = None
-    if transposed_copy:
+    if out is not None:
+        q, s = out[0], out[1]
+        if transposed_copy:
+            qT, sT = out[2], out[3]
+    else:
+        q = torch.empty((rows, cols), dtype=torch.int8, device=x.device)
+        s = torch.empty((max(rows // block, 0), max(cols // block, 0)), dtype=torch.float32, device=x.device)
+    if transposed_copy and out is None:
         qT = torch.empty((cols, rows), dtype=torch.int8, device=x.device)
         sT = torch.empty((max(cols // block, 0), max(rows // block, 0)), dtype=torch.float32, device=x.device)
     _check(lib.jf_quantize_block(_ptr(x), 0 if x.dtype == torch.float32 else 1, rows, cols, cols, block, _ptr(q), cols,
@@ -106,79 +114,83 @@ def jf_quantize_block(x, block=32, transposed_copy=False):
     return (q, s, qT, sT) if transposed_copy else (q, s)
 
 
-def _linear(fn, a, sa, b, sb, N, C, D, block, out_shape, want_q, want_f32):
+def _linear(fn, a, sa, b, sb, N, C, D, block, out_shape, want_q, want_f32, out=None):
     dev = a.device
-    q = torch.empty(out_shape, dtype=torch.int8, device=dev) if want_q else None
-    s = torch.empty((out_shape[0] // block, out_shape[1] // block), dtype=torch.float32, device=dev) if want_q else None
-    f = torch.empty(out_shape, dtype=torch.float32, device=dev) if want_f32 else None
+    if out is not None:
+        q, s, f = out
+    else:
+        q = torch.empty(out_shape, dtype=torch.int8, device=dev) if want_q else None
+        s = torch.empty((out_shape[0] // block, out_shape[1] // block), dtype=torch.float32, device=dev) if want_q else None
+        f = torch.empty(out_shape, dtype=torch.float32, device=dev) if want_f32 else None
     _check(fn(_ptr(a), _ptr(sa), _ptr(b), _ptr(sb), N, C, D, block, _ptr(q), _ptr(s), _ptr(f), None, 0, _stream()))
     return q, s, f
 
 
-def jf_linear_fwd(X, SX, W, SW, block=32, want_f32=False):
+def jf_linear_fwd(X, SX, W, SW, block=32, want_f32=False, out=None):
     """Y = X W^T.  X (N,C) int8, W (D,C) int8 -> (Y int8 (N,D), SY, Y_f32 or None)."""
     _dev(X, torch.int8, 2), _dev(W, torch.int8, 2), _dev(SX, torch.float32, 2), _dev(SW, torch.float32, 2)
     N, C = X.shape
     D = W.shape[0]
     if W.shape[1] != C:
         raise JetfireError(2, "X and W disagree on C")
-    return _linear(load_library().jf_linear_fwd, X, SX, W, SW, N, C, D, block, (N, D), True, want_f32)
+    return _linear(load_library().jf_linear_fwd, X, SX, W, SW, N, C, D, block, (N, D), True, want_f32, out)
 
 
-def jf_linear_dgrad(dY, SdY, W, SW, block=32, want_f32=False):
+def jf_linear_dgrad(dY, SdY, W, SW, block=32, want_f32=False, out=None):
     """dX = dY W.  dY (N,D) int8, W (D,C) int8 -> (dX int8 (N,C), SdX, dX_f32 or None)."""
     _dev(dY, torch.int8, 2), _dev(W, torch.int8, 2), _dev(SdY, torch.float32, 2), _dev(SW, torch.float32, 2)
     N, D = dY.shape
     C = W.shape[1]
     if W.shape[0] != D:
         raise JetfireError(2, "dY and W disagree on D")
-    return _linear(load_library().jf_linear_dgrad, dY, SdY, W, SW, N, C, D, block, (N, C), True, want_f32)
+    return _linear(load_library().jf_linear_dgrad, dY, SdY, W, SW, N, C, D, block, (N, C), True, want_f32, out)
 
 
-def jf_linear_wgrad(dY, SdY, X, SX, block=32, want_q=True, want_f32=False):
+def jf_linear_wgrad(dY, SdY, X, SX, block=32, want_q=True, want_f32=False, out=None):
     """dW = dY^T X.  dY (N,D) int8, X (N,C) int8 -> (dW int8 (D,C) or None, SdW or None, dW_f32 or None)."""
     _dev(dY, torch.int8, 2), _dev(X, torch.int8, 2), _dev(SdY, torch.float32, 2), _dev(SX, torch.float32, 2)
     N, D = dY.shape
     C = X.shape[1]
     if X.shape[0] != N:
         raise JetfireError(2, "dY and X disagree on N")
-    return _linear(load_library().jf_linear_wgrad, dY, SdY, X, SX, N, C, D, block, (D, C), want_q, want_f32)
+    return _linear(load_library().jf_linear_wgrad, dY, SdY, X, SX, N, C, D, block, (D, C), want_q, want_f32, out)
 
 
-def jf_gelu_q(X, SX, block=32):
+def jf_gelu_q(X, SX, block=32, out=None):
     _dev(X, torch.int8, 2), _dev(SX, torch.float32, 2)
     N, C = X.shape
-    Y = torch.empty_like(X)
-    SY = torch.empty_like(SX)
+    Y, SY = out if out is not None else (torch.empty_like(X), torch.empty_like(SX))
     _check(load_library().jf_gelu_q(_ptr(X), _ptr(SX), N, C, block, _ptr(Y), _ptr(SY), _stream()))
     return Y, SY
 
 
-def jf_gelu_q_bwd(dY, SdY, X, SX, block=32):
+def jf_gelu_q_bwd(dY, SdY, X, SX, block=32, out=None):
     _dev(X, torch.int8, 2), _dev(SX, torch.float32, 2), _dev(dY, torch.int8, 2), _dev(SdY, torch.float32, 2)
     N, C = X.shape
     if dY.shape != X.shape:
         raise JetfireError(2, "dY and X shapes differ")
-    dX = torch.empty_like(X)
-    SdX = torch.empty_like(SX)
+    dX, SdX = out if out is not None else (torch.empty_like(X), torch.empty_like(SX))
     _check(load_library().jf_gelu_q_bwd(_ptr(dY), _ptr(SdY), _ptr(X), _ptr(SX), N, C, block, _ptr(dX), _ptr(SdX),
                                         _stream()))
     return dX, SdX
 
 
-def jf_layernorm_q(X, SX, gamma, beta, eps=1e-5, block=32):
+def jf_layernorm_q(X, SX, gamma, beta, eps=1e-5, block=32, out=None):
     _dev(X, torch.int8, 2), _dev(SX, torch.float32, 2), _dev(gamma, torch.float32, 1), _dev(beta, torch.float32, 1)
     N, C = X.shape
-    Y = torch.empty_like(X)
-    SY = torch.empty_like(SX)
-    mean = torch.empty((N,), dtype=torch.float32, device=X.device)
-    rstd = torch.empty((N,), dtype=torch.float32, device=X.device)
+    if out is not None:
+        Y, SY, mean, rstd = out
+    else:
+        Y = torch.empty_like(X)
+        SY = torch.empty_like(SX)
+        mean = torch.empty((N,), dtype=torch.float32, device=X.device)
+        rstd = torch.empty((N,), dtype=torch.float32, device=X.device)
     _check(load_library().jf_layernorm_q(_ptr(X), _ptr(SX), _ptr(gamma), _ptr(beta), eps, N, C, block, _ptr(Y),
                                          _ptr(SY), _ptr(mean), _ptr(rstd), _stream()))
     return Y, SY, mean, rstd
 
 
-def jf_layernorm_q_bwd(dY, SdY, X, SX, gamma, mean, rstd, block=32, workspace=None):
+def jf_layernorm_q_bwd(dY, SdY, X, SX, gamma, mean, rstd, block=32, workspace=None, out=None):
     _dev(X, torch.int8, 2), _dev(SX, torch.float32, 2), _dev(dY, torch.int8, 2), _dev(SdY, torch.float32, 2)
     _dev(gamma, torch.float32, 1), _dev(mean, torch.float32, 1), _dev(rstd, torch.float32, 1)
     N, C = X.shape
@@ -187,10 +199,13 @@ def jf_layernorm_q_bwd(dY, SdY, X, SX, gamma, mean, rstd, block=32, workspace=No
     need = jf_workspace_bytes(JF_OP_LAYERNORM_BWD, N, C, 0, block)
     if workspace is None:
         workspace = torch.empty((max(need, 16),), dtype=torch.uint8, device=X.device)
-    dX = torch.empty_like(X)
-    SdX = torch.empty_like(SX)
-    dgamma = torch.empty((C,), dtype=torch.float32, device=X.device)
-    dbeta = torch.empty((C,), dtype=torch.float32, device=X.device)
+    if out is not None:
+        dX, SdX, dgamma, dbeta = out
+    else:
+        dX = torch.empty_like(X)
+        SdX = torch.empty_like(SX)
+        dgamma = torch.empty((C,), dtype=torch.float32, device=X.device)
+        dbeta = torch.empty((C,), dtype=torch.float32, device=X.device)
     _check(load_library().jf_layernorm_q_bwd(_ptr(dY), _ptr(SdY), _ptr(X), _ptr(SX), _ptr(gamma), _ptr(mean),
                                              _ptr(rstd), N, C, block, _ptr(dX), _ptr(SdX), _ptr(dgamma), _ptr(dbeta),
                                              _ptr(workspace), workspace.numel(), _stream()))

@@ -17,6 +17,8 @@
 // (Eq. 1) in registers.  The MFMA operands are swapped (rows of Bm feed the
 // "A" port) so that a lane ends up with 4 consecutive output columns of one
 // output row per register quad: codes pack into dwords without shuffles.
+#include <type_traits>
+
 #include "jf_common.hpp"
 
 namespace jf {
@@ -37,205 +39,350 @@ struct GemmArgs {
   int dump_kb;
 };
 
-// KC = bytes of K staged per LDS stage: 64 (two MFMA K steps), 128 for B = 128 so that a stage
-// always holds whole quantization blocks and block boundaries are known at compile time.
+// ---------------------------------------------------------------------------------------------
+// LDS staging.  A stage holds KC bytes of K for both operand tiles: KC = 64 (two MFMA K steps), or
+// 128 for B = 128 so that a stage always holds whole quantization blocks and block boundaries are
+// known at compile time.  Tiles go global -> LDS with global_load_lds_dwordx4: no VGPR staging, no
+// ds_write; the 64 lanes of one such instruction fill 64 consecutive 16-byte LDS slots, so the
+// layout cannot be padded.  Bank conflicts are avoided by an XOR swizzle instead: the tile is a
+// matrix of 16-byte chunks with CPR chunks per row, and chunk c of row r lives in slot
+// r*CPR + (c ^ swz(r)); swz makes 8 consecutive rows at a fixed c cover all 8 bank groups, which
+// is what both ds_read_b128 (K-major operand) and ds_read_b64_tr_b8 (M-major operand) need.
 template <int TILE, bool KMAJOR, int KC>
 struct TileLayout {
-  static constexpr int kRows = KMAJOR ? TILE : KC;
-  static constexpr int kStride = (KMAJOR ? KC : TILE) + 16;  // 16 * odd: conflict-free b128 / tr_b64 reads
-  static constexpr int kBytes = kRows * kStride;
-  static constexpr int kChunks = TILE * KC / 16;             // 16-byte chunks per stage
+  static constexpr int kRows = KMAJOR ? TILE : KC;            // LDS rows: output rows, or K rows
+  static constexpr int kCPR = (KMAJOR ? KC : TILE) / 16;      // 16-byte chunks per LDS row
+  static constexpr int kSlots = kRows * kCPR;
+  static constexpr int kBytes = kSlots * 16;
+  static_assert(kCPR == 4 || kCPR == 8, "swizzle is written for 64- or 128-byte rows");
+  static __device__ __forceinline__ int swz(int r) { return (r / (8 / kCPR)) % kCPR; }
+  static __device__ __forceinline__ int slot(int r, int c) { return r * kCPR + (c ^ swz(r)); }
 };
 
-// Copy description of one 16-byte chunk c of a stage: where it comes from and where it lands in LDS.
+typedef __attribute__((address_space(3))) void* lds_ptr;
+typedef const __attribute__((address_space(1))) void* gbl_ptr;
+typedef __attribute__((address_space(3))) v2i* lds_v2i;
+typedef __attribute__((address_space(3))) v4i* lds_v4i;
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) v4f* lds_v4f;
+
+// Per-lane LDS byte offsets of an operand's MFMA fragments inside a stage buffer.  Everything that
+// does not depend on the lane is a compile-time immediate added at the read, so the main loop spends
+// no vector ALU on addressing.  K-major: the K step j toggles a swizzled chunk bit (one offset per
+// j) and the sub-tile adds a constant; M-major: the sub-tile toggles swizzled bits (one offset per
+// sub-tile of the wave) and the K step adds a constant.
+template <int TILE, bool KMAJOR, int KC, int NSUB>
+struct FragAddr {
+  typedef TileLayout<TILE, KMAJOR, KC> L;
+  static constexpr int kN = KMAJOR ? KC / 32 : NSUB;
+  int off[kN];
+  __device__ __forceinline__ void init(int sub0, int lane) {
+    if (KMAJOR) {
+#pragma unroll
+      for (int j = 0; j < kN; ++j) off[j] = 16 * L::slot(sub0 * 32 + (lane & 31), 2 * j + (lane >> 5));
+    } else {
+      // ds_read_b64_tr_b8: within 16 lanes, lane 2r+h points at 8 bytes (columns 8h..8h+7) of row r;
+      // lane c receives column c of that 8 x 16 byte matrix.  Two reads give 16 consecutive K.
+      const int i = lane & 15, g = lane >> 4;
+#pragma unroll
+      for (int u = 0; u < kN; ++u)
+        off[u] = 16 * L::slot(16 * (g >> 1) + (i >> 1), (sub0 + u) * 2 + (g & 1)) + 8 * (i & 1);
+    }
+  }
+  // fragment of sub-tile u (relative to the wave's first), K step j, from the stage buffer at `tile`
+  __device__ __forceinline__ v4i read(const int8_t* tile, int u, int j) const {
+    if (KMAJOR) {
+      return *(lds_v4i)(tile + off[j] + u * (32 * L::kCPR * 16));
+    } else {
+      const int8_t* p = tile + off[u] + j * (32 * L::kCPR * 16);
+      v2i lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i)(p));
+      v2i hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i)(p + 8 * L::kCPR * 16));
+      v4i r = {lo[0], lo[1], hi[0], hi[1]};
+      return r;
+    }
+  }
+};
+
+// Global byte offset of the chunk that belongs in LDS slot `slot_idx` of a stage starting at K offset k0.
+// Out-of-range rows / columns / K are clamped to valid addresses: what they deliver only reaches
+// outputs that are never stored (or K steps that are never run), so no zero fill is needed.
 template <int TILE, bool KMAJOR, int KC>
-__device__ __forceinline__ void chunk_coords(int c, int& outer, int& kk, int& lds_off) {
+__device__ __forceinline__ int64_t chunk_offset(int slot_idx, int o0, int k0, int outer_dim, int K, int64_t ld) {
+  typedef TileLayout<TILE, KMAJOR, KC> L;
+  const int r = slot_idx / L::kCPR, c = (slot_idx % L::kCPR) ^ L::swz(r);
   if (KMAJOR) {
-    const int row = c / (KC / 16), kc = c % (KC / 16);
-    outer = row;
-    kk = 16 * kc;
-    lds_off = row * TileLayout<TILE, true, KC>::kStride + 16 * kc;
+    const int row = min(o0 + r, outer_dim - 1), kk = min(k0 + 16 * c, K - 16);
+    return (int64_t)row * ld + kk;
   } else {
-    const int krow = c / (TILE / 16), mc = c % (TILE / 16);
-    outer = 16 * mc;
-    kk = krow;
-    lds_off = krow * TileLayout<TILE, false, KC>::kStride + 16 * mc;
+    const int krow = min(k0 + r, K - 1), col = min(o0 + 16 * c, outer_dim - 16);
+    return (int64_t)krow * ld + col;
   }
 }
 
-// One MFMA operand fragment (16 bytes of K for row lane%32) of the 32-row sub-tile `sub`, K step j of the stage.
-template <int TILE, bool KMAJOR, int KC>
-__device__ __forceinline__ v4i read_frag(const int8_t* tile, int sub, int j, int lane) {
-  typedef __attribute__((address_space(3))) v2i* lds_v2i;
-  if (KMAJOR) {
-    const int8_t* p = tile + (sub * 32 + (lane & 31)) * TileLayout<TILE, true, KC>::kStride + j * 32 + 16 * (lane >> 5);
-    return *reinterpret_cast<const v4i*>(p);
-  } else {
-    // ds_read_b64_tr_b8: within 16 lanes, lane 2r+h points at 8 bytes (columns 8h..8h+7) of row r;
-    // lane c receives column c of that 8 x 16 byte matrix.
-    const int i = lane & 15, g = lane >> 4;
-    const int krow = j * 32 + 16 * (g >> 1) + (i >> 1);
-    const int mcol = sub * 32 + 16 * (g & 1) + 8 * (i & 1);
-    const int8_t* p = tile + krow * TileLayout<TILE, false, KC>::kStride + mcol;
-    v2i lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i)(p));
-    v2i hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i)(p + 8 * TileLayout<TILE, false, KC>::kStride));
-    v4i r = {lo[0], lo[1], hi[0], hi[1]};
-    return r;
+// acc += t * (float)v for one 32x32 sub-block (Sec. 5.3): 16 int->float conversions and 16 FMAs per lane.
+// The fused multiply-add is written as v_fmac_f32 so that it updates the accumulator register in place;
+// left to itself the register allocator ping-pongs the 64 accumulators between two register sets.
+__device__ __forceinline__ void fold(float (&acc)[16], const v16i& v, float t) {
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    const float c = (float)v[r];
+    asm("v_fmac_f32 %0, %1, %2" : "+v"(acc[r]) : "v"(t), "v"(c));
   }
 }
 
-template <int B, int WM, int WN, int WGM, int WGN, bool AK, bool BK, bool DUMP>
-__global__ void __launch_bounds__(64 * WGM * WGN, 2) gemm_kernel(const GemmArgs g) {
-  constexpr int NT = 64 * WGM * WGN;
+// WMIN = minimum resident waves per SIMD the register allocation must allow.
+template <int B, int WM, int WN, int WGM, int WGN, bool AK, bool BK, bool DUMP, int WMIN>
+__global__ void __launch_bounds__(64 * WGM * WGN, WMIN) gemm_kernel(const GemmArgs g) {
+  constexpr int NW = WGM * WGN;
   constexpr int TM = 32 * WM * WGM, TN = 32 * WN * WGN;
   constexpr int KPB = B / 32;  // MFMA K steps per quantization block
   constexpr int KC = B == 128 ? 128 : 64;
   constexpr int SPS = KC / 32;  // MFMA K steps per stage
+  constexpr int NTILE = WM * WN;
   typedef TileLayout<TM, AK, KC> LA;
   typedef TileLayout<TN, BK, KC> LB;
-  constexpr int CA = (LA::kChunks + NT - 1) / NT, CB = (LB::kChunks + NT - 1) / NT;
-  constexpr int NSA = (TM / 32) * SPS, NSB = (TN / 32) * SPS;  // scales staged per stage: [32-row granule][K step]
+  constexpr int CA = LA::kSlots / (64 * NW), CB = LB::kSlots / (64 * NW);  // load instructions per wave and stage
+  static_assert(LA::kSlots % (64 * NW) == 0 && LB::kSlots % (64 * NW) == 0, "whole load instructions per wave");
   static_assert(B == 32 || (TM % B == 0 && TN % B == 0), "tile must hold whole quantization blocks");
-  static_assert(NSA + NSB <= NT, "one scale per thread");
+  constexpr int STAGE_BYTES = LA::kBytes + LB::kBytes;
 
-  __shared__ __align__(16) int8_t s_tiles[2][LA::kBytes + LB::kBytes];
-  __shared__ float s_scales[2][NSA + NSB];
+  // Stages in the LDS ring: one being read, the rest in flight.  Three stages of a 128x128 tile with KC = 128
+  // would not fit the 160 KB of LDS, so B = 128 runs a ring of two.
+  constexpr int NBUF = (KC == 128 && STAGE_BYTES > 40 * 1024) ? 2 : 3;
+  // One LDS variable per ring slot: the compiler tracks direct-to-LDS loads per variable, so a read of
+  // one slot does not make it wait for the loads still flying into the other slots.
+  __shared__ __align__(1024) int8_t s_tile0[STAGE_BYTES];
+  __shared__ __align__(1024) int8_t s_tile1[STAGE_BYTES];
+  __shared__ __align__(1024) int8_t s_tile2[NBUF > 2 ? STAGE_BYTES : 16];
+  auto tile_buf = [&](int buf) -> int8_t* { return buf == 0 ? s_tile0 : (buf == 1 ? s_tile1 : s_tile2); };
   __shared__ float s_amax[TM / 32][TN / 32];
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm0 = (wave / WGN) * WM, wn0 = (wave % WGN) * WN;  // first 32-granule of this wave inside the tile
-  const int tiles_n = (g.Nn + TN - 1) / TN;
-  const int m0 = (blockIdx.x / tiles_n) * TM, n0 = (blockIdx.x % tiles_n) * TN;
 
-  v4i pa[CA], pb[CB];
-  float psc = 0.0f;
-
-  auto gload = [&](int k0) {
-#pragma unroll
-    for (int i = 0; i < CA; ++i) {
-      const int c = tid + i * NT;
-      int outer, kk, off;
-      chunk_coords<TM, AK, KC>(c, outer, kk, off);
-      const bool ok = (LA::kChunks % NT == 0 || c < LA::kChunks) && (m0 + outer < g.M) && (k0 + kk < g.K);
-      const int8_t* p = AK ? g.A + (int64_t)(m0 + outer) * g.lda + (k0 + kk) : g.A + (int64_t)(k0 + kk) * g.lda + (m0 + outer);
-      v4i z = {0, 0, 0, 0};
-      pa[i] = ok ? *reinterpret_cast<const v4i*>(p) : z;
-    }
-#pragma unroll
-    for (int i = 0; i < CB; ++i) {
-      const int c = tid + i * NT;
-      int outer, kk, off;
-      chunk_coords<TN, BK, KC>(c, outer, kk, off);
-      const bool ok = (LB::kChunks % NT == 0 || c < LB::kChunks) && (n0 + outer < g.Nn) && (k0 + kk < g.K);
-      const int8_t* p = BK ? g.Bm + (int64_t)(n0 + outer) * g.ldb + (k0 + kk) : g.Bm + (int64_t)(k0 + kk) * g.ldb + (n0 + outer);
-      v4i z = {0, 0, 0, 0};
-      pb[i] = ok ? *reinterpret_cast<const v4i*>(p) : z;
-    }
-    if (!DUMP && tid < NSA + NSB) {
-      const bool isA = tid < NSA;
-      const int e = isA ? tid : tid - NSA;
-      const int gr = (isA ? m0 : n0) + 32 * (e / SPS), gk = k0 + 32 * (e % SPS);
-      const bool ok = gr < (isA ? g.M : g.Nn) && gk < g.K;
-      const float* S = isA ? g.SA : g.SB;
-      const int sp = isA ? g.sa_p : g.sb_p, sk = isA ? g.sa_k : g.sb_k;
-      psc = ok ? S[(int64_t)(gr / B) * sp + (int64_t)(gk / B) * sk] : 0.0f;
-    }
-  };
-  auto lstore = [&](int buf) {
-    int8_t* ta = s_tiles[buf];
-    int8_t* tb = ta + LA::kBytes;
-#pragma unroll
-    for (int i = 0; i < CA; ++i) {
-      const int c = tid + i * NT;
-      int outer, kk, off;
-      chunk_coords<TM, AK, KC>(c, outer, kk, off);
-      if (LA::kChunks % NT == 0 || c < LA::kChunks) *reinterpret_cast<v4i*>(ta + off) = pa[i];
-    }
-#pragma unroll
-    for (int i = 0; i < CB; ++i) {
-      const int c = tid + i * NT;
-      int outer, kk, off;
-      chunk_coords<TN, BK, KC>(c, outer, kk, off);
-      if (LB::kChunks % NT == 0 || c < LB::kChunks) *reinterpret_cast<v4i*>(tb + off) = pb[i];
-    }
-    if (!DUMP && tid < NSA + NSB) s_scales[buf][tid] = psc;
-  };
-
-  float acc[WM][WN][16];
-  v16i vi[WM][WN];
-  const v16i zero16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-  for (int a = 0; a < WM; ++a)
-#pragma unroll
-    for (int b = 0; b < WN; ++b) {
-      vi[a][b] = zero16;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.0f;
-    }
+  // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  Renumber them so that
+  // every XCD works on one contiguous band of tiles and re-reads its operands from its own L2.
+  const int ntiles = gridDim.x, tiles_n = (g.Nn + TN - 1) / TN;
+  const int xcd = blockIdx.x & 7, idx = blockIdx.x >> 3;
+  const int tile = xcd * (ntiles >> 3) + min(xcd, ntiles & 7) + idx;
+  const int m0 = (tile / tiles_n) * TM, n0 = (tile % tiles_n) * TN;
 
   const int nsteps = g.K / 32;
   const int nstages = (g.K + KC - 1) / KC;
-  gload(0);
-  lstore(0);
-  __syncthreads();
-  for (int s = 0; s < nstages; ++s) {
-    const int buf = s & 1;
-    if (s + 1 < nstages) gload((s + 1) * KC);
-    const int8_t* ta = s_tiles[buf];
-    const int8_t* tb = ta + LA::kBytes;
+
+  // Per-lane source pointers of stage 0 (loop invariant); a later stage adds k0 (K-major) or k0*ld (M-major).
+  const int8_t* srcA[CA];
+  const int8_t* srcB[CB];
+#pragma unroll
+  for (int i = 0; i < CA; ++i) srcA[i] = g.A + chunk_offset<TM, AK, KC>((i * NW + wave) * 64 + lane, m0, 0, g.M, g.K, g.lda);
+#pragma unroll
+  for (int i = 0; i < CB; ++i) srcB[i] = g.Bm + chunk_offset<TN, BK, KC>((i * NW + wave) * 64 + lane, n0, 0, g.Nn, g.K, g.ldb);
+  const int64_t kstrideA = AK ? 1 : g.lda, kstrideB = BK ? 1 : g.ldb;
+  // Block scales are wave-uniform: they are read with scalar loads straight into SGPRs, one stage ahead
+  // (sa_n / sb_n), so they cost neither LDS traffic nor vector-memory slots.  Index [a][j]: sub-tile a of the
+  // wave, K step j of the stage.  Granules or K steps outside the matrix are clamped (their products are unused).
+  float sa_c[WM][SPS], sb_c[WN][SPS], sa_n[WM][SPS], sb_n[WN][SPS];
+  int sa_row[WM], sb_row[WN];
+#pragma unroll
+  for (int a = 0; a < WM; ++a) sa_row[a] = (min(m0 + 32 * (wm0 + a), g.M - 32) / B) * g.sa_p;
+#pragma unroll
+  for (int b = 0; b < WN; ++b) sb_row[b] = (min(n0 + 32 * (wn0 + b), g.Nn - 32) / B) * g.sb_p;
+  // The grids are read through the constant address space: they are never written by this kernel, and a
+  // uniform load from that space is selected as a scalar load.
+  typedef const __attribute__((address_space(4))) float* const_f32_ptr;
+  const const_f32_ptr SAc = (const_f32_ptr)g.SA, SBc = (const_f32_ptr)g.SB;
+  auto load_scales = [&](int s) {
+    if (DUMP) return;
 #pragma unroll
     for (int j = 0; j < SPS; ++j) {
-      const int step = s * SPS + j;
-      if (step < nsteps) {
+      const int kb = min(s * KC + 32 * j, g.K - 32) / B;
+#pragma unroll
+      for (int a = 0; a < WM; ++a) sa_n[a][j] = SAc[sa_row[a] + (int64_t)kb * g.sa_k];
+#pragma unroll
+      for (int b = 0; b < WN; ++b) sb_n[b][j] = SBc[sb_row[b] + (int64_t)kb * g.sb_k];
+    }
+  };
+  auto rotate_scales = [&]() {
+#pragma unroll
+    for (int j = 0; j < SPS; ++j) {
+#pragma unroll
+      for (int a = 0; a < WM; ++a) sa_c[a][j] = sa_n[a][j];
+#pragma unroll
+      for (int b = 0; b < WN; ++b) sb_c[b][j] = sb_n[b][j];
+    }
+  };
+
+  // Issue the direct-to-LDS loads of stage s into buffer buf (0 or 1).
+  auto issue = [&](int s, int buf) {
+    const int k0 = s * KC;
+    int8_t* ta = tile_buf(buf);
+    int8_t* tb = ta + LA::kBytes;
+    if (k0 + KC <= g.K) {
+#pragma unroll
+      for (int i = 0; i < CA; ++i)
+        __builtin_amdgcn_global_load_lds((gbl_ptr)(srcA[i] + k0 * kstrideA), (lds_ptr)(ta + 1024 * (i * NW + wave)), 16, 0, 0);
+#pragma unroll
+      for (int i = 0; i < CB; ++i)
+        __builtin_amdgcn_global_load_lds((gbl_ptr)(srcB[i] + k0 * kstrideB), (lds_ptr)(tb + 1024 * (i * NW + wave)), 16, 0, 0);
+    } else {  // the last stage of a K that is an odd multiple of 32: clamp what lies beyond K
+#pragma unroll
+      for (int i = 0; i < CA; ++i) {
+        const int64_t off = chunk_offset<TM, AK, KC>((i * NW + wave) * 64 + lane, m0, k0, g.M, g.K, g.lda);
+        __builtin_amdgcn_global_load_lds((gbl_ptr)(g.A + off), (lds_ptr)(ta + 1024 * (i * NW + wave)), 16, 0, 0);
+      }
+#pragma unroll
+      for (int i = 0; i < CB; ++i) {
+        const int64_t off = chunk_offset<TN, BK, KC>((i * NW + wave) * 64 + lane, n0, k0, g.Nn, g.K, g.ldb);
+        __builtin_amdgcn_global_load_lds((gbl_ptr)(g.Bm + off), (lds_ptr)(tb + 1024 * (i * NW + wave)), 16, 0, 0);
+      }
+    }
+  };
+
+  FragAddr<TM, AK, KC, WM> addrA;
+  FragAddr<TN, BK, KC, WN> addrB;
+  addrA.init(wm0, lane);
+  addrB.init(wn0, lane);
+
+  float acc[WM][WN][16];
+#pragma unroll
+  for (int a = 0; a < WM; ++a)
+#pragma unroll
+    for (int b = 0; b < WN; ++b)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.0f;
+  const v16i zero16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+  v16i vchain[KPB > 1 ? NTILE : 1];  // INT32 tiles carried across K steps (B > 32 only)
+
+  auto dump_tile = [&](const v16i& v, int a, int b) {
+    const int m = m0 + 32 * (wm0 + a) + (lane & 31);
+    const int nb = n0 + 32 * (wn0 + b) + 4 * (lane >> 5);
+    if (m < g.M && nb < g.Nn) {
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        v4i o = {v[4 * q4], v[4 * q4 + 1], v[4 * q4 + 2], v[4 * q4 + 3]};
+        *reinterpret_cast<v4i*>(g.dump + (int64_t)m * g.Nn + nb + 8 * q4) = o;
+      }
+    }
+  };
+
+  // One stage (STEPS K steps) out of buffer `buf`.
+  auto compute = [&](int s, int buf, auto steps_tag) {
+    constexpr int STEPS = decltype(steps_tag)::value;
+    const int8_t* ta = tile_buf(buf);
+    const int8_t* tb = ta + LA::kBytes;
+    // this stage's scales were fetched during the previous stage; fetch the next stage's now
+    rotate_scales();
+    if (s + 1 < nstages) load_scales(s + 1);
+    float (&sa)[WM][SPS] = sa_c;
+    float (&sb)[WN][SPS] = sb_c;
+    if constexpr (KPB == 1) {
+      // B = 32: every MFMA result is folded right away.  Two INT32 tiles rotate: the MFMA of the next
+      // tile is issued before the 32 conversions/FMAs of the current one, so the matrix pipe runs in
+      // the shadow of the vector ALU work of the same wave.
+      v4i fa[2][WM], fb[2][WN];
+      v16i vi[2];
+#pragma unroll
+      for (int a = 0; a < WM; ++a) fa[0][a] = addrA.read(ta, a, 0);
+#pragma unroll
+      for (int b = 0; b < WN; ++b) fb[0][b] = addrB.read(tb, b, 0);
+      vi[0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[0][0], fa[0][0], zero16, 0, 0, 0);
+#pragma unroll
+      for (int j = 0; j < STEPS; ++j) {
+        if (j + 1 < STEPS) {
+#pragma unroll
+          for (int a = 0; a < WM; ++a) fa[(j + 1) & 1][a] = addrA.read(ta, a, j + 1);
+#pragma unroll
+          for (int b = 0; b < WN; ++b) fb[(j + 1) & 1][b] = addrB.read(tb, b, j + 1);
+        }
+#pragma unroll
+        for (int t = 0; t < NTILE; ++t) {
+          const int cur = (j * NTILE + t) & 1;
+          const int a = t / WN, b = t % WN;
+          if (t + 1 < NTILE) {
+            const int a1 = (t + 1) / WN, b1 = (t + 1) % WN;
+            vi[cur ^ 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[j & 1][b1], fa[j & 1][a1], zero16, 0, 0, 0);
+          } else if (j + 1 < STEPS) {
+            vi[cur ^ 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[(j + 1) & 1][0], fa[(j + 1) & 1][0], zero16, 0, 0, 0);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+          if (DUMP) {
+            if (s * SPS + j == g.dump_kb) dump_tile(vi[cur], a, b);
+          } else {
+            fold(acc[a][b], vi[cur], sa[a][j] * sb[b][j]);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+    } else {
+      // B = 64 / 128: the INT32 tiles accumulate over KPB K steps inside the MFMA, then are folded.
+#pragma unroll
+      for (int j = 0; j < STEPS; ++j) {
         v4i fa[WM], fb[WN];
 #pragma unroll
-        for (int a = 0; a < WM; ++a) fa[a] = read_frag<TM, AK, KC>(ta, wm0 + a, j, lane);
+        for (int a = 0; a < WM; ++a) fa[a] = addrA.read(ta, a, j);
 #pragma unroll
-        for (int b = 0; b < WN; ++b) fb[b] = read_frag<TN, BK, KC>(tb, wn0 + b, j, lane);
+        for (int b = 0; b < WN; ++b) fb[b] = addrB.read(tb, b, j);
 #pragma unroll
-        for (int a = 0; a < WM; ++a)
-#pragma unroll
-          for (int b = 0; b < WN; ++b)
-            vi[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[b], fa[a], (j % KPB == 0) ? zero16 : vi[a][b], 0, 0, 0);
+        for (int t = 0; t < NTILE; ++t)
+          vchain[t] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[t % WN], fa[t / WN], (j % KPB == 0) ? zero16 : vchain[t], 0, 0, 0);
         if ((j + 1) % KPB == 0) {  // end of a quantization block along K (a stage holds whole blocks)
-          if (DUMP) {
-            if (step / KPB == g.dump_kb) {
 #pragma unroll
-              for (int a = 0; a < WM; ++a)
-#pragma unroll
-                for (int b = 0; b < WN; ++b) {
-                  const int m = m0 + 32 * (wm0 + a) + (lane & 31);
-                  const int nb = n0 + 32 * (wn0 + b) + 4 * (lane >> 5);
-                  if (m < g.M && nb < g.Nn) {
-#pragma unroll
-                    for (int q4 = 0; q4 < 4; ++q4) {
-                      v4i o = {vi[a][b][4 * q4], vi[a][b][4 * q4 + 1], vi[a][b][4 * q4 + 2], vi[a][b][4 * q4 + 3]};
-                      *reinterpret_cast<v4i*>(g.dump + (int64_t)m * g.Nn + nb + 8 * q4) = o;
-                    }
-                  }
-                }
+          for (int t = 0; t < NTILE; ++t) {
+            if (DUMP) {
+              if ((s * SPS + j) / KPB == g.dump_kb) dump_tile(vchain[t], t / WN, t % WN);
+            } else {
+              fold(acc[t / WN][t % WN], vchain[t], sa[t / WN][j] * sb[t % WN][j]);
             }
-          } else {
-            float sa[WM], sb[WN];
-#pragma unroll
-            for (int a = 0; a < WM; ++a) sa[a] = s_scales[buf][(wm0 + a) * SPS + j];
-#pragma unroll
-            for (int b = 0; b < WN; ++b) sb[b] = s_scales[buf][NSA + (wn0 + b) * SPS + j];
-#pragma unroll
-            for (int a = 0; a < WM; ++a)
-#pragma unroll
-              for (int b = 0; b < WN; ++b) {
-                const float t = sa[a] * sb[b];
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[a][b][r] = __builtin_fmaf(t, (float)vi[a][b][r], acc[a][b][r]);
-              }
           }
         }
       }
     }
-    if (s + 1 < nstages) lstore(buf ^ 1);
-    __syncthreads();
+  };
+
+  // Stage loop over the ring of NBUF LDS buffers: while stage s is computed, stages s+1 .. s+NBUF-1
+  // are in flight, which covers the L2 latency even when a stage is only two K steps long.  The loop
+  // is unrolled NBUF times so that every LDS address is a compile-time immediate and the accumulators
+  // stay in the same registers; the last (at most NBUF) stages run from a generic copy after the loop.
+  constexpr int LOADS = CA + CB;  // vector-memory instructions per wave and stage
+  constexpr int AHEAD = NBUF - 1;                   // stages issued ahead of the one being computed
+  static_assert(LOADS * (AHEAD - 1) <= 63, "vmcnt immediate");
+  // End of a stage: wait for this wave's own loads of the stage that is read next, then meet the other waves.
+  // A bare s_barrier is used instead of __syncthreads(): the fence of the latter makes the compiler drain
+  // every outstanding load (vmcnt(0)), including the stage that is meant to stay in flight.  Ordering is kept
+  // by hand: the asm is a compiler barrier for memory accesses, each wave has consumed all its LDS reads of the
+  // finished stage before it arrives, and direct-to-LDS loads are counted by vmcnt.
+  auto wait_loads = [&](int in_flight_stages) {  // at most that many of the youngest stages stay outstanding
+    if (in_flight_stages == 0) asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(LOADS) : "memory");
+  };
+  static_assert(AHEAD <= 2, "wait_loads handles at most one stage left in flight");
+  const std::integral_constant<int, SPS> whole_tag;
+  const std::integral_constant<int, 1> half_tag;
+  const int nwhole = g.K / KC;
+  load_scales(0);
+#pragma unroll
+  for (int i = 0; i < AHEAD; ++i)
+    if (i < nstages) issue(i, i);
+  wait_loads(nstages > 1 ? AHEAD - 1 : 0);
+  int s = 0;
+  // inside this loop stage s + NBUF + AHEAD - 1 .. exist for every issue, and every computed stage is whole
+  for (; s + NBUF <= nwhole && s + NBUF + AHEAD - 1 < nstages; s += NBUF) {
+#pragma unroll
+    for (int u = 0; u < NBUF; ++u) {
+      issue(s + u + AHEAD, (u + AHEAD) % NBUF);
+      if (u == 0) compute(s + u, 0, whole_tag);
+      else if (u == 1) compute(s + u, 1, whole_tag);
+      else compute(s + u, 2, whole_tag);
+      wait_loads(AHEAD - 1);
+    }
+  }
+  for (int buf = s % NBUF; s < nstages; ++s, buf = (buf + 1 == NBUF ? 0 : buf + 1)) {
+    const bool more = s + AHEAD < nstages;
+    if (more) issue(s + AHEAD, (buf + AHEAD) % NBUF);
+    if (s < nwhole) compute(s, buf, whole_tag);
+    else if constexpr (KPB == 1 && SPS > 1) compute(s, buf, half_tag);
+    wait_loads(more ? AHEAD - 1 : 0);
   }
   if (DUMP) return;
 
@@ -289,20 +436,43 @@ __global__ void __launch_bounds__(64 * WGM * WGN, 2) gemm_kernel(const GemmArgs 
         float scale, inv;
         block_scale(amax[a][b], scale, inv);
         if (lane == 0 && (mrow0 % B) == 0 && (ncol0 % B) == 0) g.Os[(int64_t)(mrow0 / B) * ln + ncol0 / B] = scale;
+        // Codes go to LDS first (the operand ring is idle now: every wave has passed the last stage barrier),
+        // laid out as the TM x TN byte tile with its 16-byte chunks XOR-swizzled by the row, so that the
+        // tile can be written to memory as whole rows.
+        const int row = 32 * (wm0 + a) + (lane & 31);
 #pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4)
-          *reinterpret_cast<uint32_t*>(g.Oq + (int64_t)m * g.Nn + nb + 8 * q4) =
+        for (int q4 = 0; q4 < 4; ++q4) {
+          const int col = 32 * (wn0 + b) + 8 * q4 + 4 * (lane >> 5);
+          const int chunk = (col >> 4) ^ (row & (TN / 16 - 1));
+          *reinterpret_cast<uint32_t*>(s_tile0 + row * TN + 16 * chunk + (col & 15)) =
               quantize4(acc[a][b][4 * q4], acc[a][b][4 * q4 + 1], acc[a][b][4 * q4 + 2], acc[a][b][4 * q4 + 3], inv);
+        }
       }
     }
+  if (g.Oq) {
+    // TN / 16 consecutive lanes write one TN-byte row of the tile: full 128-byte lines for the 128-wide tile.
+    static_assert(TM * TN <= STAGE_BYTES, "the code tile is staged in one ring slot");
+    __syncthreads();
+    constexpr int CPRO = TN / 16;
+#pragma unroll
+    for (int i = 0; i < (TM * CPRO) / (64 * NW); ++i) {
+      const int id = i * 64 * NW + tid;
+      const int row = id / CPRO, c = id % CPRO;
+      if (m0 + row < g.M && n0 + 16 * c < g.Nn) {
+        const uint4 v = *reinterpret_cast<const uint4*>(s_tile0 + row * TN + 16 * (c ^ (row & (CPRO - 1))));
+        *reinterpret_cast<uint4*>(g.Oq + (int64_t)(m0 + row) * g.Nn + n0 + 16 * c) = v;
+      }
+    }
+  }
 }
 
 // --------------------------------------------------------------------- host
 template <int B, int WM, int WN, int WGM, int WGN, bool AK, bool BK, bool DUMP>
 static void launch_cfg(const GemmArgs& a, hipStream_t st) {
   constexpr int TM = 32 * WM * WGM, TN = 32 * WN * WGN;
+  constexpr int WMIN = (WM * WN >= 4) ? (B == 32 ? 3 : 2) : 4;
   const int tiles = ((a.M + TM - 1) / TM) * ((a.Nn + TN - 1) / TN);
-  hipLaunchKernelGGL((gemm_kernel<B, WM, WN, WGM, WGN, AK, BK, DUMP>), dim3(tiles), dim3(64 * WGM * WGN), 0, st, a);
+  hipLaunchKernelGGL((gemm_kernel<B, WM, WN, WGM, WGN, AK, BK, DUMP, WMIN>), dim3(tiles), dim3(64 * WGM * WGN), 0, st, a);
 }
 
 // Two tile shapes: 128x128 (each wave 2x2 sub-blocks) and 64x64 (each wave one sub-block).  The INT8 path is

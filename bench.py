@@ -35,7 +35,8 @@ def parse_args():
     ap.add_argument("--in-features", type=int, default=768)
     ap.add_argument("--out-features", type=int, default=3072)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
-    ap.add_argument("--cpu-sample-tokens", type=int, default=512)
+    ap.add_argument("--cpu-sample-tokens", type=int, default=4096)
+    ap.add_argument("--graph", action="store_true", help="also time the step replayed from a captured HIP graph")
     return ap.parse_args()
 
 
@@ -142,6 +143,25 @@ def main():
     dt = time.perf_counter() - t0
     ms_per_step = dt / args.steps * 1e3
 
+    graph_ms = None
+    if args.graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step(False)
+            gr = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(gr, stream=side):
+                step(False)
+            for _ in range(5):
+                gr.replay()
+            side.synchronize()
+            t0g = time.perf_counter()
+            for _ in range(args.steps):
+                gr.replay()
+            side.synchronize()
+            graph_ms = (time.perf_counter() - t0g) / args.steps * 1e3
+        torch.cuda.current_stream().wait_stream(side)
+
     gemm_ms = [e0.elapsed_time(e1) for e0, e1 in gemm_events]
     gemm_avg_ms = sum(gemm_ms) / len(gemm_ms)
     per_gemm = [sum(gemm_ms[i::3]) / args.steps for i in range(3)]
@@ -149,17 +169,27 @@ def main():
     achieved = gemm_ops / (gemm_avg_ms * 1e-3) * 1e-12
 
     # ---- per-op GB/s of the memory-bound kernels (separate, untimed-for-`value` loops with events)
-    def op_ms(fn, reps=50):
-        for _ in range(5):
+    def op_ms(fn, reps=20, replays=5):
+        """Average duration of one launch: `reps` back-to-back launches captured in a HIP graph (so that the
+        host-side launch cost does not hide the kernel time), replayed a few times between two events."""
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
             fn()
-        e0 = torch.cuda.Event(enable_timing=True)
-        e1 = torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(reps):
-            fn()
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / reps
+            gr = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(gr, stream=side):
+                for _ in range(reps):
+                    fn()
+            gr.replay()
+            e0 = torch.cuda.Event(enable_timing=True)
+            e1 = torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(replays):
+                gr.replay()
+            e1.record()
+            side.synchronize()
+        torch.cuda.current_stream().wait_stream(side)
+        return e0.elapsed_time(e1) / (reps * replays)
 
     sb = 4.0 / (B * B)
     ops = {
@@ -210,6 +240,8 @@ def main():
         "memory_bound_ops": memops,
         "paper_context": "paper reports ratios only: 1.42x transformer-layer speedup, 1.49x activation memory vs FP16 on RTX 4090",
     }
+    if graph_ms is not None:
+        out["graph_replay_ms_per_step"] = round(graph_ms, 5)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args, N, C, D, B)
     print(json.dumps(out), flush=True)

@@ -1,31 +1,71 @@
 // INT8-in / INT8-out GELU and LayerNorm, forward and backward (Sec. 6, Alg. 2, App. A).
 //
-// HBM-bound element-wise kernels.  Work is organised in strips of 8 rows x 128
-// columns per wave instruction: lane = (row l/8, 16-byte column chunk l%8), so
-// every row segment a wave touches is one full 128-byte line, loaded and stored
-// as 16 bytes per lane.
+// These kernels move 2-3 bytes per element, so at HBM speed a compute unit has only about ten vector
+// ALU instructions to spend per element.  Two ideas keep them inside that budget:
+//   * GELU: within one quantization block the input takes at most 255 values (code * block scale), so
+//     GELU (or its derivative) is tabulated once per block in LDS and every element is a table lookup
+//     indexed by its code byte -- the dequantize step of Alg. 2 and the erf evaluation collapse into it;
+//   * LayerNorm: row sums come from exact integer dot products of the codes (v_dot4), scaled per block,
+//     which is the row-partials scheme of App. A applied to the INT8 input itself.
 #include "jf_common.hpp"
 
 namespace jf {
 
-__device__ __forceinline__ float std_normal_cdf(float x) { return 0.5f * erfcf(-0.70710678118654752f * x); }
-__device__ __forceinline__ float std_normal_pdf(float x) { return 0.39894228040143268f * expf(-0.5f * x * x); }
-
-struct GeluFwd {
-  static constexpr bool kHasGrad = false;
-  static __device__ __forceinline__ float apply(float x, float) { return x * std_normal_cdf(x); }
+// ------------------------------------------------------------------------------------------------
+// Standard normal upper tail Q(a) = Phi(-a), a >= 0, with small RELATIVE error (about 1e-6) over the
+// whole FP32 range, so that a block lying entirely in the negative tail still gets an accurate scale.
+//   erfc(z) = t * exp(P(t) - z^2),  t = 1 / (1 + z/2),  P a degree-9 polynomial fitted by least squares
+//   on Chebyshev nodes against log(erfcx(z)/t) for 0 <= z <= 9.5 (max error of P: 4.5e-8).
+// z^2 = a^2/2 is formed exactly (product + FMA residual) and the base-2 exponent is split in a large part H and
+// a small part m, each exponentiated separately; otherwise the FP32 rounding of an exponent of size z^2
+// would cost log2(z^2) bits of the result.  Also returns exp(-z^2) (needed by the GELU derivative).
+struct TailEval {
+  float q;      // Q(a)
+  float ez;     // exp(-a^2/2)
 };
-struct GeluBwd {
-  static constexpr bool kHasGrad = true;
-  static __device__ __forceinline__ float apply(float x, float g) { return g * (x * std_normal_pdf(x) + std_normal_cdf(x)); }
-};
+__device__ __forceinline__ TailEval normal_tail(float a) {
+  const float L2E = 1.4426950408889634f;
+  const float z = a * 0.70710678118654752f;
+  const float t = __builtin_amdgcn_rcpf(__builtin_fmaf(0.5f, z, 1.0f));
+  float p = 1.409394439e-01f;
+  p = __builtin_fmaf(p, t, -6.589882025e-01f);
+  p = __builtin_fmaf(p, t, 1.105068749e+00f);
+  p = __builtin_fmaf(p, t, -6.270881863e-01f);
+  p = __builtin_fmaf(p, t, -1.378501274e-01f);
+  p = __builtin_fmaf(p, t, 3.206818161e-02f);
+  p = __builtin_fmaf(p, t, 2.404601430e-02f);
+  p = __builtin_fmaf(p, t, 3.888682058e-01f);
+  p = __builtin_fmaf(p, t, 9.983709344e-01f);
+  p = __builtin_fmaf(p, t, -1.265434969e+00f);
+  const float aa = a * a;
+  const float s1 = 0.5f * aa;
+  const float s2 = 0.5f * __builtin_fmaf(a, a, -aa);     // z^2 = a^2/2 = s1 + s2 exactly
+  const float H = -s1 * L2E;
+  const float r1 = __builtin_fmaf(-s1, L2E, -H);         // -s1*log2(e) = H + r1 exactly
+  const float corr = __builtin_fmaf(-s2, L2E, r1);       // exponent of exp(-z^2) beyond H (tiny)
+  const float e1 = __builtin_amdgcn_exp2f(H);
+  TailEval r;
+  r.ez = e1 * __builtin_fmaf(corr, 0.6931471805599453f, 1.0f);
+  r.q = 0.5f * t * e1 * __builtin_amdgcn_exp2f(__builtin_fmaf(p, L2E, corr));
+  return r;
+}
 
-__device__ __forceinline__ void unpack16(const uint4& p, float s, float (&v)[16]) {
-  const uint32_t w[4] = {p.x, p.y, p.z, p.w};
-#pragma unroll
-  for (int d = 0; d < 4; ++d)
-#pragma unroll
-    for (int b = 0; b < 4; ++b) v[4 * d + b] = byte_to_float(w[d], b) * s;
+// GELU(x) = x Phi(x) = max(x, 0) - |x| Q(|x|)     (App. A)
+__device__ __forceinline__ float gelu_value(float x) {
+  const float a = fabsf(x);
+  return fmaxf(x, 0.0f) - a * normal_tail(a).q;
+}
+// dGELU/dx = x phi(x) + Phi(x),  phi(x) = exp(-x^2/2) / sqrt(2 pi),  Phi(x) = x > 0 ? 1 - Q : Q     (App. A)
+__device__ __forceinline__ float gelu_slope(float x) {
+  const float a = fabsf(x);
+  const TailEval te = normal_tail(a);
+  const float cdf = x > 0.0f ? 1.0f - te.q : te.q;
+  return __builtin_fmaf(x * 0.39894228040143268f, te.ez, cdf);
+}
+
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ float amax4(float m, float a, float b, float c, float d) {
+  return fmaxf(fmaxf(m, fmaxf(fabsf(a), fabsf(b))), fmaxf(fabsf(c), fabsf(d)));
 }
 
 __device__ __forceinline__ uint4 quantize16(const float (&y)[16], float inv) {
@@ -37,62 +77,93 @@ __device__ __forceinline__ uint4 quantize16(const float (&y)[16], float inv) {
   return o;
 }
 
-__device__ __forceinline__ float amax16(const float (&y)[16]) {
-  float m = 0.0f;
+// 16 codes -> (code + 128) as float: one XOR per dword flips the sign bits, then each byte converts
+// with v_cvt_f32_ubyteN.  The caller folds the -128 into its fused multiply-add.
+__device__ __forceinline__ void unpack16_biased(const uint4& p, float (&u)[16]) {
+  const uint32_t w[4] = {p.x ^ 0x80808080u, p.y ^ 0x80808080u, p.z ^ 0x80808080u, p.w ^ 0x80808080u};
 #pragma unroll
-  for (int e = 0; e < 16; ++e) m = fmaxf(m, fabsf(y[e]));
-  return m;
+  for (int d = 0; d < 4; ++d) {
+    u[4 * d + 0] = (float)(w[d] & 0xffu);
+    u[4 * d + 1] = (float)((w[d] >> 8) & 0xffu);
+    u[4 * d + 2] = (float)((w[d] >> 16) & 0xffu);
+    u[4 * d + 3] = (float)(w[d] >> 24);
+  }
 }
 
-// Reduce a per-lane value over the lanes of a wave that share a quantization block column:
-// all 8 row lanes (bits 3..5) and the B/16 (<= 8) chunk lanes of the block (low bits).
+// Reduce over the lanes of a wave that share a quantization-block column in the (8 rows x 8 chunks)
+// strip mapping: all 8 row lanes (bits 3..5) and the B/16 (<= 8) chunk lanes of the block (low bits).
 template <int B>
 __device__ __forceinline__ float strip_block_max(float m) {
   constexpr int CH = B >= 128 ? 7 : (B == 64 ? 3 : 1);
   return wave_group_max<56 | CH>(m);
 }
 
-// Element-wise operator of Alg. 2.  One workgroup (B/32 waves... fixed 4 waves) covers B rows x 128 columns:
-// wave w handles rows [w*B/4, (w+1)*B/4) in B/32 passes of 8 rows.
-template <typename Op, int B>
-__global__ void __launch_bounds__(256) eltwise_kernel(const int8_t* __restrict__ X, const float* __restrict__ SX,
-                                                       const int8_t* __restrict__ G, const float* __restrict__ SG,
-                                                       int rows, int cols, int8_t* __restrict__ Y,
-                                                       float* __restrict__ SY) {
-  constexpr int P = B / 32;  // 8-row passes per wave
+// ------------------------------------------------------------------------------------------------
+// GELU forward / backward.  One workgroup of four waves owns B rows x 128 columns = 128/min(B,128)
+// quantization blocks; wave w owns rows [w*B/4, (w+1)*B/4) in B/32 passes of 8 rows, lane = (row l/8,
+// 16-byte chunk l%8), so every row segment is a full 128-byte line.
+template <bool BWD, int B>
+__global__ void __launch_bounds__(256) gelu_kernel(const int8_t* __restrict__ X, const float* __restrict__ SX,
+                                                    const int8_t* __restrict__ G, const float* __restrict__ SG,
+                                                    int rows, int cols, int8_t* __restrict__ Y, float* __restrict__ SY) {
+  constexpr int P = B / 32;                  // 8-row passes per wave
+  constexpr int NTAB = B >= 128 ? 1 : 128 / B;  // quantization blocks (= tables) per workgroup
+  __shared__ float s_tab[NTAB][256];         // indexed by the code byte taken as unsigned
   __shared__ float s_amax[4][4];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int ch = lane & 7, rsub = lane >> 3;
   const int c0 = blockIdx.x * 128, col = c0 + 16 * ch;
   const int r0 = blockIdx.y * B + wave * (B / 4);
   const bool col_ok = col < cols;  // cols % 32 == 0 and chunks are 16 wide: a 32-column group is all in or all out
-  const int lc = cols / B;
-  const int bj = col / B, bi = blockIdx.y;
+  const int lc = cols / B, bi = blockIdx.y;
+
+  // tabulate f(code * scale) for the 256 byte values of each block of this workgroup
+#pragma unroll
+  for (int k = 0; k < NTAB; ++k) {
+    const int bcol = c0 + k * B;
+    if (bcol < cols) {
+      const float s = SX[(int64_t)bi * lc + bcol / B];
+      const float x = (float)(int8_t)threadIdx.x * s;
+      s_tab[k][threadIdx.x] = BWD ? gelu_slope(x) : gelu_value(x);
+    }
+  }
+  __syncthreads();
 
   float y[P][16];
   float m = 0.0f;
   if (col_ok) {
-    const float sx = SX[(int64_t)bi * lc + bj];
-    const float sg = Op::kHasGrad ? SG[(int64_t)bi * lc + bj] : 0.0f;
+    const float* tab = s_tab[(16 * ch) / B];
+    float sg = 0.0f, sg128 = 0.0f;
+    if (BWD) {
+      sg = SG[(int64_t)bi * lc + col / B];
+      sg128 = -128.0f * sg;
+    }
 #pragma unroll
     for (int p = 0; p < P; ++p) {
       const int row = r0 + 8 * p + rsub;
       const uint4 px = *reinterpret_cast<const uint4*>(X + (int64_t)row * cols + col);
-      float x[16], gr[16];
-      unpack16(px, sx, x);
-      if (Op::kHasGrad) {
+      const uint32_t w[4] = {px.x, px.y, px.z, px.w};
+      float f[16];
+#pragma unroll
+      for (int d = 0; d < 4; ++d) {
+        f[4 * d + 0] = tab[w[d] & 0xffu];
+        f[4 * d + 1] = tab[(w[d] >> 8) & 0xffu];
+        f[4 * d + 2] = tab[(w[d] >> 16) & 0xffu];
+        f[4 * d + 3] = tab[w[d] >> 24];
+      }
+      if (BWD) {
         const uint4 pg = *reinterpret_cast<const uint4*>(G + (int64_t)row * cols + col);
-        unpack16(pg, sg, gr);
+        float ug[16];
+        unpack16_biased(pg, ug);
+#pragma unroll
+        for (int e = 0; e < 16; ++e) y[p][e] = __builtin_fmaf(ug[e], sg, sg128) * f[e];
+      } else {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) y[p][e] = f[e];
       }
 #pragma unroll
-      for (int e = 0; e < 16; ++e) y[p][e] = Op::apply(x[e], Op::kHasGrad ? gr[e] : 0.0f);
-      m = fmaxf(m, amax16(y[p]));
+      for (int e = 0; e < 16; e += 4) m = amax4(m, y[p][e], y[p][e + 1], y[p][e + 2], y[p][e + 3]);
     }
-  } else {
-#pragma unroll
-    for (int p = 0; p < P; ++p)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) y[p][e] = 0.0f;
   }
   m = strip_block_max<B>(m);
   // s_amax[wave][32-column group]; for B >= 64 the in-wave reduction already covered the whole block width
@@ -102,7 +173,7 @@ __global__ void __launch_bounds__(256) eltwise_kernel(const int8_t* __restrict__
   float scale, inv;
   block_scale(m, scale, inv);
   if (!col_ok) return;
-  if (wave == 0 && rsub == 0 && (col % B) == 0) SY[(int64_t)bi * lc + bj] = scale;
+  if (wave == 0 && rsub == 0 && (col % B) == 0) SY[(int64_t)bi * lc + col / B] = scale;
 #pragma unroll
   for (int p = 0; p < P; ++p) {
     const int row = r0 + 8 * p + rsub;
@@ -110,112 +181,157 @@ __global__ void __launch_bounds__(256) eltwise_kernel(const int8_t* __restrict__
   }
 }
 
-// ------------------------------------------------------------------ LayerNorm forward
-// One workgroup owns B rows and all C columns.  Pass 1: exact per-(row, 16-column chunk) integer sums of
-// codes and squared codes (v_dot4), scaled by the block scale and accumulated per row in FP64 -- the same
-// row-partials scheme as App. A, computed from the INT8 input itself.  Pass 2: per 128-column group,
-// normalise, find the block max-abs across the four waves, quantize, store.
-template <int B>
-__global__ void __launch_bounds__(256) layernorm_fwd_kernel(const int8_t* __restrict__ X, const float* __restrict__ SX,
-                                                             const float* __restrict__ gamma,
-                                                             const float* __restrict__ beta, float eps, int rows,
-                                                             int cols, int8_t* __restrict__ Y, float* __restrict__ SY,
-                                                             float* __restrict__ mean_out, float* __restrict__ rstd_out) {
-  constexpr int P = B / 32;
-  __shared__ float s_amax[2][4][4];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int ch = lane & 7, rsub = lane >> 3;
-  const int r0 = blockIdx.x * B + wave * (B / 4);
-  const int lc = cols / B, bi = blockIdx.x;
-  const int ngroups = (cols + 127) / 128;
+// ------------------------------------------------------------------------------------------------
+// LayerNorm.  One workgroup of four waves owns B rows and all C columns; wave w owns rows
+// [w*B/4, (w+1)*B/4).  Lane l of a wave owns the 16-byte chunks l, l+64, ... of each of its rows, so a
+// row is read as contiguous 1 KB runs and per-column quantities (gamma, beta, column sums) stay in
+// registers while the wave walks down its rows.  NIT = ceil(C / 1024) chunks per lane and row.
 
-  float mu[P], rs[P];
+// exact sums of the 16 codes of a chunk and of their squares
+__device__ __forceinline__ void chunk_moments(const uint4& p, int& s1, int& s2) {
+  s1 = __builtin_amdgcn_sdot4((int)p.x, 0x01010101, 0, false);
+  s1 = __builtin_amdgcn_sdot4((int)p.y, 0x01010101, s1, false);
+  s1 = __builtin_amdgcn_sdot4((int)p.z, 0x01010101, s1, false);
+  s1 = __builtin_amdgcn_sdot4((int)p.w, 0x01010101, s1, false);
+  s2 = __builtin_amdgcn_sdot4((int)p.x, (int)p.x, 0, false);
+  s2 = __builtin_amdgcn_sdot4((int)p.y, (int)p.y, s2, false);
+  s2 = __builtin_amdgcn_sdot4((int)p.z, (int)p.z, s2, false);
+  s2 = __builtin_amdgcn_sdot4((int)p.w, (int)p.w, s2, false);
+}
+
+__device__ __forceinline__ void load16f(const float* p, float (&v)[16]) {
 #pragma unroll
-  for (int p = 0; p < P; ++p) {
-    const int row = r0 + 8 * p + rsub;
-    double sum = 0.0, sq = 0.0;
-    for (int gidx = 0; gidx < ngroups; ++gidx) {
-      const int col = gidx * 128 + 16 * ch;
-      if (col < cols) {
-        const uint4 px = *reinterpret_cast<const uint4*>(X + (int64_t)row * cols + col);
-        const float sx = SX[(int64_t)bi * lc + col / B];
-        int s1 = 0, s2 = 0;
-        s1 = __builtin_amdgcn_sdot4((int)px.x, 0x01010101, s1, false);
-        s1 = __builtin_amdgcn_sdot4((int)px.y, 0x01010101, s1, false);
-        s1 = __builtin_amdgcn_sdot4((int)px.z, 0x01010101, s1, false);
-        s1 = __builtin_amdgcn_sdot4((int)px.w, 0x01010101, s1, false);
-        s2 = __builtin_amdgcn_sdot4((int)px.x, (int)px.x, s2, false);
-        s2 = __builtin_amdgcn_sdot4((int)px.y, (int)px.y, s2, false);
-        s2 = __builtin_amdgcn_sdot4((int)px.z, (int)px.z, s2, false);
-        s2 = __builtin_amdgcn_sdot4((int)px.w, (int)px.w, s2, false);
-        const double sd = (double)sx;
-        sum += sd * (double)s1;
-        sq += sd * sd * (double)s2;
+  for (int d = 0; d < 4; ++d) {
+    const float4 t = *reinterpret_cast<const float4*>(p + 4 * d);
+    v[4 * d] = t.x; v[4 * d + 1] = t.y; v[4 * d + 2] = t.z; v[4 * d + 3] = t.w;
+  }
+}
+
+// Forward: NW = 16 waves per workgroup (a workgroup is alone on its compute unit, since there are only
+// N/B of them), RW = B/16 rows per wave.  If the wave's rows fit in registers (KEEP) they are read once.
+template <int B, int NIT>
+__global__ void __launch_bounds__(1024) layernorm_fwd_kernel(const int8_t* __restrict__ X, const float* __restrict__ SX,
+                                                              const float* __restrict__ gamma,
+                                                              const float* __restrict__ beta, float eps, int rows,
+                                                              int cols, int8_t* __restrict__ Y, float* __restrict__ SY,
+                                                              float* __restrict__ mean_out, float* __restrict__ rstd_out) {
+  constexpr int NW = 16, RW = B / NW;
+  constexpr bool KEEP = RW * NIT <= 8;
+  extern __shared__ float s_dyn[];  // [NW][C/32] per-wave block max-abs
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int r0 = blockIdx.x * B + wave * RW;
+  const int lc = cols / B, bi = blockIdx.x, nchunks = cols / 16, ngran = cols / 32;
+  float* s_amax = s_dyn;
+
+  bool ok[NIT];
+  float sx[NIT];
+#pragma unroll
+  for (int it = 0; it < NIT; ++it) {
+    const int c = lane + 64 * it;
+    ok[it] = c < nchunks;
+    sx[it] = ok[it] ? SX[(int64_t)bi * lc + (16 * c) / B] : 0.0f;
+  }
+  uint4 xs[KEEP ? RW : 1][NIT];
+  auto chunk = [&](int r, int it) -> uint4 {
+    if (KEEP) return xs[r][it];
+    return *reinterpret_cast<const uint4*>(X + (int64_t)(r0 + r) * cols + 16 * (lane + 64 * it));
+  };
+  if (KEEP) {
+#pragma unroll
+    for (int r = 0; r < RW; ++r)
+#pragma unroll
+      for (int it = 0; it < NIT; ++it)
+        xs[r][it] = ok[it] ? *reinterpret_cast<const uint4*>(X + (int64_t)(r0 + r) * cols + 16 * (lane + 64 * it))
+                           : make_uint4(0, 0, 0, 0);
+  }
+
+  // sweep 1: row statistics from exact integer chunk sums, combined in FP64
+  float k1[RW][NIT], k2[RW];  // xhat = u * k1 + k2 with u = code + 128
+#pragma unroll
+  for (int r = 0; r < RW; ++r) {
+    double ds = 0.0, dq = 0.0;
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+      if (ok[it]) {
+        int s1, s2;
+        chunk_moments(chunk(r, it), s1, s2);
+        const double sd = (double)sx[it];
+        ds += sd * (double)s1;
+        dq += sd * sd * (double)s2;
       }
     }
-    sum = wave_group_sum_f64<7>(sum);
-    sq = wave_group_sum_f64<7>(sq);
+    const double sum = wave_group_sum_f64<63>(ds);
+    const double sq = wave_group_sum_f64<63>(dq);
     const double mean = sum / (double)cols;
     double var = sq / (double)cols - mean * mean;
     var = var > 0.0 ? var : 0.0;
     const double rstd = 1.0 / sqrt(var + (double)eps);
-    mu[p] = (float)mean;
-    rs[p] = (float)rstd;
-    if (ch == 0) {
-      mean_out[row] = mu[p];
-      rstd_out[row] = rs[p];
+    const float mu = (float)mean, rs = (float)rstd;
+    if (lane == 0) {
+      mean_out[r0 + r] = mu;
+      rstd_out[r0 + r] = rs;
     }
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) k1[r][it] = sx[it] * rs;
+    k2[r] = -mu * rs;
   }
 
-  for (int gidx = 0; gidx < ngroups; ++gidx) {
-    const int col = gidx * 128 + 16 * ch;
-    const bool col_ok = col < cols;
-    float y[P][16];
+  // sweep 2: block max-abs of y = xhat * gamma + beta
+  constexpr int LM = B / 16 - 1;  // lanes of one block column: mask 1, 3 or 7
+#pragma unroll
+  for (int it = 0; it < NIT; ++it) {
     float m = 0.0f;
-    if (col_ok) {
-      const float sx = SX[(int64_t)bi * lc + col / B];
+    if (ok[it]) {
       float gm[16], bt[16];
+      load16f(gamma + 16 * (lane + 64 * it), gm);
+      load16f(beta + 16 * (lane + 64 * it), bt);
 #pragma unroll
-      for (int d = 0; d < 4; ++d) {
-        const float4 g4 = *reinterpret_cast<const float4*>(gamma + col + 4 * d);
-        const float4 b4 = *reinterpret_cast<const float4*>(beta + col + 4 * d);
-        gm[4 * d] = g4.x; gm[4 * d + 1] = g4.y; gm[4 * d + 2] = g4.z; gm[4 * d + 3] = g4.w;
-        bt[4 * d] = b4.x; bt[4 * d + 1] = b4.y; bt[4 * d + 2] = b4.z; bt[4 * d + 3] = b4.w;
-      }
+      for (int r = 0; r < RW; ++r) {
+        float u[16];
+        unpack16_biased(chunk(r, it), u);
+        const float kb = __builtin_fmaf(-128.0f, k1[r][it], k2[r]);
 #pragma unroll
-      for (int p = 0; p < P; ++p) {
-        const int row = r0 + 8 * p + rsub;
-        const uint4 px = *reinterpret_cast<const uint4*>(X + (int64_t)row * cols + col);
-        float x[16];
-        unpack16(px, sx, x);
-#pragma unroll
-        for (int e = 0; e < 16; ++e) y[p][e] = __builtin_fmaf((x[e] - mu[p]) * rs[p], gm[e], bt[e]);
-        m = fmaxf(m, amax16(y[p]));
+        for (int e = 0; e < 16; ++e)
+          m = fmaxf(m, fabsf(__builtin_fmaf(__builtin_fmaf(u[e], k1[r][it], kb), gm[e], bt[e])));
       }
     }
-    m = strip_block_max<B>(m);
-    const int buf = gidx & 1;
-    if ((lane & 57) == 0) s_amax[buf][wave][ch >> 1] = m;
-    __syncthreads();
-    m = fmaxf(fmaxf(s_amax[buf][0][ch >> 1], s_amax[buf][1][ch >> 1]), fmaxf(s_amax[buf][2][ch >> 1], s_amax[buf][3][ch >> 1]));
-    float scale, inv;
-    block_scale(m, scale, inv);
-    if (col_ok) {
-      if (wave == 0 && rsub == 0 && (col % B) == 0) SY[(int64_t)bi * lc + col / B] = scale;
+    m = wave_group_max<LM>(m);
+    const int c = lane + 64 * it;
+    if (ok[it] && (c & 1) == 0) s_amax[wave * ngran + (c >> 1)] = m;
+  }
+  __syncthreads();
+
+  // sweep 3: recompute y, quantize, store
 #pragma unroll
-      for (int p = 0; p < P; ++p) {
-        const int row = r0 + 8 * p + rsub;
-        *reinterpret_cast<uint4*>(Y + (int64_t)row * cols + col) = quantize16(y[p], inv);
+  for (int it = 0; it < NIT; ++it) {
+    const int c = lane + 64 * it;
+    if (ok[it]) {
+      float mm = 0.0f, scale, inv;
+#pragma unroll
+      for (int w = 0; w < NW; ++w) mm = fmaxf(mm, s_amax[w * ngran + (c >> 1)]);
+      block_scale(mm, scale, inv);
+      if (wave == 0 && ((16 * c) % B) == 0) SY[(int64_t)bi * lc + (16 * c) / B] = scale;
+      float gm[16], bt[16];
+      load16f(gamma + 16 * c, gm);
+      load16f(beta + 16 * c, bt);
+#pragma unroll
+      for (int r = 0; r < RW; ++r) {
+        float u[16], y[16];
+        unpack16_biased(chunk(r, it), u);
+        const float kb = __builtin_fmaf(-128.0f, k1[r][it], k2[r]);
+#pragma unroll
+        for (int e = 0; e < 16; ++e) y[e] = __builtin_fmaf(__builtin_fmaf(u[e], k1[r][it], kb), gm[e], bt[e]);
+        *reinterpret_cast<uint4*>(Y + (int64_t)(r0 + r) * cols + 16 * c) = quantize16(y, inv);
       }
     }
   }
 }
 
-// ------------------------------------------------------------------ LayerNorm backward
-// Same ownership.  Pass 1: per row m1 = mean_C(ghat), m2 = mean_C(ghat * xhat); per column the partial
-// sums of g * xhat and g over this workgroup's B rows go to the workspace (one row of partials per
-// workgroup, summed in a fixed order by colsum_kernel).  Pass 2: dx, block max-abs, quantize, store.
-template <int B>
+// LayerNorm backward.  Four waves per workgroup, RW = B/4 rows per wave.  Sweep 1: per row
+// m1 = mean_C(ghat), m2 = mean_C(ghat xhat), and per column the sums of g*xhat and g over this wave's
+// rows, written as one partial row per wave to the workspace.  Sweeps 2 and 3: dx = rstd (ghat - m1 -
+// xhat m2), block max-abs, quantize, store.
+template <int B, int NIT>
 __global__ void __launch_bounds__(256) layernorm_bwd_kernel(const int8_t* __restrict__ G, const float* __restrict__ SG,
                                                              const int8_t* __restrict__ X, const float* __restrict__ SX,
                                                              const float* __restrict__ gamma,
@@ -223,154 +339,195 @@ __global__ void __launch_bounds__(256) layernorm_bwd_kernel(const int8_t* __rest
                                                              const float* __restrict__ rstd_in, int rows, int cols,
                                                              int8_t* __restrict__ dX, float* __restrict__ SdX,
                                                              float* __restrict__ partials) {
-  constexpr int P = B / 32;
-  __shared__ float s_amax[2][4][4];
-  __shared__ float s_col[2][4][2][128];  // [buffer][wave][dgamma|dbeta][column of the group]
+  constexpr int NW = 4, RW = B / NW;
+  constexpr bool KEEP = RW * NIT <= 8;
+  extern __shared__ float s_dyn[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int ch = lane & 7, rsub = lane >> 3;
-  const int r0 = blockIdx.x * B + wave * (B / 4);
-  const int lc = cols / B, bi = blockIdx.x;
-  const int ngroups = (cols + 127) / 128;
-  float* part_g = partials + (int64_t)blockIdx.x * 2 * cols;
+  const int r0 = blockIdx.x * B + wave * RW;
+  const int lc = cols / B, bi = blockIdx.x, nchunks = cols / 16, ngran = cols / 32;
+  float* s_amax = s_dyn;
+  float* part_g = partials + ((int64_t)blockIdx.x * NW + wave) * 2 * cols;
   float* part_b = part_g + cols;
 
-  float mu[P], rs[P], m1[P], m2[P];
+  bool ok[NIT];
+  float sx[NIT], sg[NIT];
 #pragma unroll
-  for (int p = 0; p < P; ++p) {
-    const int row = r0 + 8 * p + rsub;
-    mu[p] = mean_in[row];
-    rs[p] = rstd_in[row];
-    m1[p] = 0.0f;
-    m2[p] = 0.0f;
+  for (int it = 0; it < NIT; ++it) {
+    const int c = lane + 64 * it;
+    ok[it] = c < nchunks;
+    sx[it] = ok[it] ? SX[(int64_t)bi * lc + (16 * c) / B] : 0.0f;
+    sg[it] = ok[it] ? SG[(int64_t)bi * lc + (16 * c) / B] : 0.0f;
   }
-  for (int gidx = 0; gidx < ngroups; ++gidx) {
-    const int col = gidx * 128 + 16 * ch;
-    const bool col_ok = col < cols;
-    float cg[16], cb[16];
+  uint4 xs[KEEP ? RW : 1][NIT], gs[KEEP ? RW : 1][NIT];
+  auto chunk_x = [&](int r, int it) -> uint4 {
+    if (KEEP) return xs[r][it];
+    return *reinterpret_cast<const uint4*>(X + (int64_t)(r0 + r) * cols + 16 * (lane + 64 * it));
+  };
+  auto chunk_g = [&](int r, int it) -> uint4 {
+    if (KEEP) return gs[r][it];
+    return *reinterpret_cast<const uint4*>(G + (int64_t)(r0 + r) * cols + 16 * (lane + 64 * it));
+  };
+  if (KEEP) {
 #pragma unroll
-    for (int e = 0; e < 16; ++e) cg[e] = cb[e] = 0.0f;
-    if (col_ok) {
-      const float sx = SX[(int64_t)bi * lc + col / B], sg = SG[(int64_t)bi * lc + col / B];
-      float gm[16];
+    for (int r = 0; r < RW; ++r)
 #pragma unroll
-      for (int d = 0; d < 4; ++d) {
-        const float4 g4 = *reinterpret_cast<const float4*>(gamma + col + 4 * d);
-        gm[4 * d] = g4.x; gm[4 * d + 1] = g4.y; gm[4 * d + 2] = g4.z; gm[4 * d + 3] = g4.w;
+      for (int it = 0; it < NIT; ++it) {
+        const int64_t off = (int64_t)(r0 + r) * cols + 16 * (lane + 64 * it);
+        xs[r][it] = ok[it] ? *reinterpret_cast<const uint4*>(X + off) : make_uint4(0, 0, 0, 0);
+        gs[r][it] = ok[it] ? *reinterpret_cast<const uint4*>(G + off) : make_uint4(0, 0, 0, 0);
       }
+  }
+  float mu[RW], rs[RW], m1[RW], m2[RW];
 #pragma unroll
-      for (int p = 0; p < P; ++p) {
-        const int row = r0 + 8 * p + rsub;
-        const uint4 px = *reinterpret_cast<const uint4*>(X + (int64_t)row * cols + col);
-        const uint4 pg = *reinterpret_cast<const uint4*>(G + (int64_t)row * cols + col);
-        float x[16], gr[16];
-        unpack16(px, sx, x);
-        unpack16(pg, sg, gr);
+  for (int r = 0; r < RW; ++r) {
+    mu[r] = mean_in[r0 + r];
+    rs[r] = rstd_in[r0 + r];
+    m1[r] = m2[r] = 0.0f;
+  }
+
+  // sweep 1
+#pragma unroll
+  for (int it = 0; it < NIT; ++it) {
+    if (ok[it]) {
+      const int c = lane + 64 * it;
+      float gm[16], cg[16], cb[16];
+      load16f(gamma + 16 * c, gm);
+#pragma unroll
+      for (int e = 0; e < 16; ++e) cg[e] = cb[e] = 0.0f;
+      const float g128 = -128.0f * sg[it];
+#pragma unroll
+      for (int r = 0; r < RW; ++r) {
+        float ux[16], ug[16];
+        unpack16_biased(chunk_x(r, it), ux);
+        unpack16_biased(chunk_g(r, it), ug);
+        const float kx = sx[it] * rs[r], cx = __builtin_fmaf(-128.0f, kx, -mu[r] * rs[r]);
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-          const float xh = (x[e] - mu[p]) * rs[p];
-          const float gh = gr[e] * gm[e];
-          m1[p] += gh;
-          m2[p] = __builtin_fmaf(gh, xh, m2[p]);
-          cg[e] = __builtin_fmaf(gr[e], xh, cg[e]);
-          cb[e] += gr[e];
+          const float xh = __builtin_fmaf(ux[e], kx, cx);
+          const float gv = __builtin_fmaf(ug[e], sg[it], g128);
+          const float gh = gv * gm[e];
+          m1[r] += gh;
+          m2[r] = __builtin_fmaf(gh, xh, m2[r]);
+          cg[e] = __builtin_fmaf(gv, xh, cg[e]);
+          cb[e] += gv;
         }
       }
+#pragma unroll
+      for (int d = 0; d < 4; ++d) {
+        *reinterpret_cast<float4*>(part_g + 16 * c + 4 * d) = make_float4(cg[4 * d], cg[4 * d + 1], cg[4 * d + 2], cg[4 * d + 3]);
+        *reinterpret_cast<float4*>(part_b + 16 * c + 4 * d) = make_float4(cb[4 * d], cb[4 * d + 1], cb[4 * d + 2], cb[4 * d + 3]);
+      }
     }
-    // column partials: sum over the 8 row lanes, then over the four waves in a fixed order
-    const int buf = gidx & 1;
+  }
+  // dx = ug * a_c + ux * kxm + (a_c * -128 + krow) with a_c = rstd * sg * gamma_c
+  float kxm[RW][NIT], krow[RW][NIT];
+#pragma unroll
+  for (int r = 0; r < RW; ++r) {
+    const float q1 = wave_group_sum<63>(m1[r]) / (float)cols;
+    const float q2 = wave_group_sum<63>(m2[r]) / (float)cols;
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+      const float kx = sx[it] * rs[r], cx = __builtin_fmaf(-128.0f, kx, -mu[r] * rs[r]);
+      kxm[r][it] = -rs[r] * q2 * kx;
+      krow[r][it] = -rs[r] * __builtin_fmaf(cx, q2, q1);
+    }
+  }
+  auto dx16 = [&](int r, int it, const float (&gm)[16], float (&y)[16]) {
+    float ux[16], ug[16];
+    unpack16_biased(chunk_x(r, it), ux);
+    unpack16_biased(chunk_g(r, it), ug);
+    const float rsg = rs[r] * sg[it];
 #pragma unroll
     for (int e = 0; e < 16; ++e) {
-      cg[e] = wave_group_sum<56>(cg[e]);
-      cb[e] = wave_group_sum<56>(cb[e]);
+      const float a = rsg * gm[e];
+      const float k = __builtin_fmaf(a, -128.0f, krow[r][it]);
+      y[e] = __builtin_fmaf(ux[e], kxm[r][it], __builtin_fmaf(ug[e], a, k));
     }
-    if (rsub == 0) {
-#pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        s_col[buf][wave][0][16 * ch + e] = cg[e];
-        s_col[buf][wave][1][16 * ch + e] = cb[e];
-      }
-    }
-    __syncthreads();
-    {
-      const int which = threadIdx.x >> 7, c = threadIdx.x & 127;
-      if (gidx * 128 + c < cols) {
-        const float v = ((s_col[buf][0][which][c] + s_col[buf][1][which][c]) + s_col[buf][2][which][c]) + s_col[buf][3][which][c];
-        (which ? part_b : part_g)[gidx * 128 + c] = v;
-      }
-    }
-  }
-#pragma unroll
-  for (int p = 0; p < P; ++p) {
-    m1[p] = wave_group_sum<7>(m1[p]) / (float)cols;
-    m2[p] = wave_group_sum<7>(m2[p]) / (float)cols;
-  }
+  };
 
-  for (int gidx = 0; gidx < ngroups; ++gidx) {
-    const int col = gidx * 128 + 16 * ch;
-    const bool col_ok = col < cols;
-    float y[P][16];
+  // sweep 2
+  constexpr int LM = B / 16 - 1;
+#pragma unroll
+  for (int it = 0; it < NIT; ++it) {
     float m = 0.0f;
-    if (col_ok) {
-      const float sx = SX[(int64_t)bi * lc + col / B], sg = SG[(int64_t)bi * lc + col / B];
+    if (ok[it]) {
       float gm[16];
+      load16f(gamma + 16 * (lane + 64 * it), gm);
 #pragma unroll
-      for (int d = 0; d < 4; ++d) {
-        const float4 g4 = *reinterpret_cast<const float4*>(gamma + col + 4 * d);
-        gm[4 * d] = g4.x; gm[4 * d + 1] = g4.y; gm[4 * d + 2] = g4.z; gm[4 * d + 3] = g4.w;
-      }
+      for (int r = 0; r < RW; ++r) {
+        float y[16];
+        dx16(r, it, gm, y);
 #pragma unroll
-      for (int p = 0; p < P; ++p) {
-        const int row = r0 + 8 * p + rsub;
-        const uint4 px = *reinterpret_cast<const uint4*>(X + (int64_t)row * cols + col);
-        const uint4 pg = *reinterpret_cast<const uint4*>(G + (int64_t)row * cols + col);
-        float x[16], gr[16];
-        unpack16(px, sx, x);
-        unpack16(pg, sg, gr);
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const float xh = (x[e] - mu[p]) * rs[p];
-          const float gh = gr[e] * gm[e];
-          y[p][e] = rs[p] * ((gh - m1[p]) - xh * m2[p]);
-        }
-        m = fmaxf(m, amax16(y[p]));
+        for (int e = 0; e < 16; e += 4) m = amax4(m, y[e], y[e + 1], y[e + 2], y[e + 3]);
       }
     }
-    m = strip_block_max<B>(m);
-    const int buf = gidx & 1;
-    if ((lane & 57) == 0) s_amax[buf][wave][ch >> 1] = m;
-    __syncthreads();
-    m = fmaxf(fmaxf(s_amax[buf][0][ch >> 1], s_amax[buf][1][ch >> 1]), fmaxf(s_amax[buf][2][ch >> 1], s_amax[buf][3][ch >> 1]));
-    float scale, inv;
-    block_scale(m, scale, inv);
-    if (col_ok) {
-      if (wave == 0 && rsub == 0 && (col % B) == 0) SdX[(int64_t)bi * lc + col / B] = scale;
+    m = wave_group_max<LM>(m);
+    const int c = lane + 64 * it;
+    if (ok[it] && (c & 1) == 0) s_amax[wave * ngran + (c >> 1)] = m;
+  }
+  __syncthreads();
+
+  // sweep 3
 #pragma unroll
-      for (int p = 0; p < P; ++p) {
-        const int row = r0 + 8 * p + rsub;
-        *reinterpret_cast<uint4*>(dX + (int64_t)row * cols + col) = quantize16(y[p], inv);
+  for (int it = 0; it < NIT; ++it) {
+    const int c = lane + 64 * it;
+    if (ok[it]) {
+      float mm = 0.0f, scale, inv;
+#pragma unroll
+      for (int w = 0; w < NW; ++w) mm = fmaxf(mm, s_amax[w * ngran + (c >> 1)]);
+      block_scale(mm, scale, inv);
+      if (wave == 0 && ((16 * c) % B) == 0) SdX[(int64_t)bi * lc + (16 * c) / B] = scale;
+      float gm[16];
+      load16f(gamma + 16 * c, gm);
+#pragma unroll
+      for (int r = 0; r < RW; ++r) {
+        float y[16];
+        dx16(r, it, gm, y);
+        *reinterpret_cast<uint4*>(dX + (int64_t)(r0 + r) * cols + 16 * c) = quantize16(y, inv);
       }
     }
   }
 }
 
-// dgamma / dbeta: sum the per-workgroup partial rows in ascending order (bit-stable from run to run).
-__global__ void __launch_bounds__(256) colsum_kernel(const float* __restrict__ partials, int nparts, int cols,
-                                                      float* __restrict__ dgamma, float* __restrict__ dbeta) {
-  const int c = blockIdx.x * 256 + threadIdx.x;
-  if (c >= 2 * cols) return;
-  float acc = 0.0f;
-  for (int p = 0; p < nparts; ++p) acc += partials[(int64_t)p * 2 * cols + c];
-  if (c < cols) dgamma[c] = acc;
-  else dbeta[c - cols] = acc;
+// dgamma / dbeta: sum the per-wave partial rows in a fixed order (bit-stable from run to run).  A workgroup
+// of 16 waves owns 64 columns of the 2*C wide partial matrix; wave w sums rows w, w+16, w+32, ... (four
+// independent chains keep loads in flight), and wave 0 adds the 16 results in wave order.
+__global__ void __launch_bounds__(1024) colsum_kernel(const float* __restrict__ partials, int nparts, int cols2,
+                                                       float* __restrict__ dgamma, float* __restrict__ dbeta) {
+  __shared__ float s_part[16][64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int c = blockIdx.x * 64 + lane;
+  float acc0 = 0.0f, acc1 = 0.0f, acc2 = 0.0f, acc3 = 0.0f;
+  if (c < cols2) {
+    int p = wave;
+    for (; p + 48 < nparts; p += 64) {
+      acc0 += partials[(int64_t)p * cols2 + c];
+      acc1 += partials[(int64_t)(p + 16) * cols2 + c];
+      acc2 += partials[(int64_t)(p + 32) * cols2 + c];
+      acc3 += partials[(int64_t)(p + 48) * cols2 + c];
+    }
+    for (; p < nparts; p += 16) acc0 += partials[(int64_t)p * cols2 + c];
+  }
+  s_part[wave][lane] = (acc0 + acc1) + (acc2 + acc3);
+  __syncthreads();
+  if (wave == 0 && c < cols2) {
+    float v = 0.0f;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) v += s_part[w][lane];
+    const int half = cols2 / 2;
+    if (c < half) dgamma[c] = v;
+    else dbeta[c - half] = v;
+  }
 }
 
-template <typename Op>
-static void launch_eltwise(int block, const int8_t* X, const float* SX, const int8_t* G, const float* SG, int rows,
-                           int cols, int8_t* Y, float* SY, hipStream_t st) {
+// ------------------------------------------------------------------------------------------------ host
+template <bool BWD>
+static void launch_gelu(int block, const int8_t* X, const float* SX, const int8_t* G, const float* SG, int rows,
+                        int cols, int8_t* Y, float* SY, hipStream_t st) {
   dim3 grid((cols + 127) / 128, rows / block);
-  if (block == 32) hipLaunchKernelGGL((eltwise_kernel<Op, 32>), grid, dim3(256), 0, st, X, SX, G, SG, rows, cols, Y, SY);
-  else if (block == 64) hipLaunchKernelGGL((eltwise_kernel<Op, 64>), grid, dim3(256), 0, st, X, SX, G, SG, rows, cols, Y, SY);
-  else hipLaunchKernelGGL((eltwise_kernel<Op, 128>), grid, dim3(256), 0, st, X, SX, G, SG, rows, cols, Y, SY);
+  if (block == 32) hipLaunchKernelGGL((gelu_kernel<BWD, 32>), grid, dim3(256), 0, st, X, SX, G, SG, rows, cols, Y, SY);
+  else if (block == 64) hipLaunchKernelGGL((gelu_kernel<BWD, 64>), grid, dim3(256), 0, st, X, SX, G, SG, rows, cols, Y, SY);
+  else hipLaunchKernelGGL((gelu_kernel<BWD, 128>), grid, dim3(256), 0, st, X, SX, G, SG, rows, cols, Y, SY);
 }
 
 static int32_t check_eltwise(const void* x, const void* sx, const void* y, const void* sy, int64_t N, int64_t C,
@@ -382,6 +539,35 @@ static int32_t check_eltwise(const void* x, const void* sx, const void* y, const
   return JF_OK;
 }
 
+// LayerNorm rows are held as NIT 16-byte chunks per lane; the register budget caps NIT at 4 (C <= 4096).
+constexpr int64_t kLayerNormMaxC = 4096;
+
+template <int B, int NIT, typename... Args>
+static void launch_ln_fwd(dim3 grid, size_t lds, hipStream_t st, Args... args) {
+  hipLaunchKernelGGL((layernorm_fwd_kernel<B, NIT>), grid, dim3(1024), lds, st, args...);
+}
+template <int B, int NIT, typename... Args>
+static void launch_ln_bwd(dim3 grid, size_t lds, hipStream_t st, Args... args) {
+  hipLaunchKernelGGL((layernorm_bwd_kernel<B, NIT>), grid, dim3(256), lds, st, args...);
+}
+
+#define JF_LN_DISPATCH(FN, block, nit, ...)                                   \
+  do {                                                                        \
+    if (block == 32) {                                                        \
+      if (nit == 1) FN<32, 1>(__VA_ARGS__);                                   \
+      else if (nit == 2) FN<32, 2>(__VA_ARGS__);                              \
+      else FN<32, 4>(__VA_ARGS__);                                            \
+    } else if (block == 64) {                                                 \
+      if (nit == 1) FN<64, 1>(__VA_ARGS__);                                   \
+      else if (nit == 2) FN<64, 2>(__VA_ARGS__);                              \
+      else FN<64, 4>(__VA_ARGS__);                                            \
+    } else {                                                                  \
+      if (nit == 1) FN<128, 1>(__VA_ARGS__);                                  \
+      else if (nit == 2) FN<128, 2>(__VA_ARGS__);                             \
+      else FN<128, 4>(__VA_ARGS__);                                           \
+    }                                                                         \
+  } while (0)
+
 }  // namespace jf
 
 extern "C" int32_t jf_gelu_q(const int8_t* X, const float* SX, int64_t N, int64_t C, int32_t block, int8_t* Y,
@@ -389,7 +575,7 @@ extern "C" int32_t jf_gelu_q(const int8_t* X, const float* SX, int64_t N, int64_
   using namespace jf;
   int32_t rc = check_eltwise(X, SX, Y, SY, N, C, block);
   if (rc != JF_OK) return rc;
-  launch_eltwise<GeluFwd>(block, X, SX, nullptr, nullptr, (int)N, (int)C, Y, SY, reinterpret_cast<hipStream_t>(stream));
+  launch_gelu<false>(block, X, SX, nullptr, nullptr, (int)N, (int)C, Y, SY, reinterpret_cast<hipStream_t>(stream));
   return launch_status();
 }
 
@@ -400,7 +586,7 @@ extern "C" int32_t jf_gelu_q_bwd(const int8_t* dY, const float* SdY, const int8_
   if (rc != JF_OK) return rc;
   if (!dY || !SdY) return JF_ERR_NULL;
   if (!aligned16(dY) || !aligned4(SdY)) return JF_ERR_ALIGN;
-  launch_eltwise<GeluBwd>(block, X, SX, dY, SdY, (int)N, (int)C, dX, SdX, reinterpret_cast<hipStream_t>(stream));
+  launch_gelu<true>(block, X, SX, dY, SdY, (int)N, (int)C, dX, SdX, reinterpret_cast<hipStream_t>(stream));
   return launch_status();
 }
 
@@ -411,12 +597,13 @@ extern "C" int32_t jf_layernorm_q(const int8_t* X, const float* SX, const float*
   int32_t rc = check_eltwise(X, SX, Y, SY, N, C, block);
   if (rc != JF_OK) return rc;
   if (!gamma || !beta || !mean || !rstd) return JF_ERR_NULL;
+  if (C > kLayerNormMaxC) return JF_ERR_SHAPE;
   if (!aligned16(gamma) || !aligned16(beta) || !aligned4(mean) || !aligned4(rstd)) return JF_ERR_ALIGN;
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-  dim3 grid((unsigned)(N / block));
-  if (block == 32) hipLaunchKernelGGL((layernorm_fwd_kernel<32>), grid, dim3(256), 0, st, X, SX, gamma, beta, eps, (int)N, (int)C, Y, SY, mean, rstd);
-  else if (block == 64) hipLaunchKernelGGL((layernorm_fwd_kernel<64>), grid, dim3(256), 0, st, X, SX, gamma, beta, eps, (int)N, (int)C, Y, SY, mean, rstd);
-  else hipLaunchKernelGGL((layernorm_fwd_kernel<128>), grid, dim3(256), 0, st, X, SX, gamma, beta, eps, (int)N, (int)C, Y, SY, mean, rstd);
+  const dim3 grid((unsigned)(N / block));
+  const int nit = (int)((C + 1023) / 1024);
+  const size_t lds = 16 * (size_t)(C / 32) * sizeof(float);
+  JF_LN_DISPATCH(launch_ln_fwd, block, nit, grid, lds, st, X, SX, gamma, beta, eps, (int)N, (int)C, Y, SY, mean, rstd);
   return launch_status();
 }
 
@@ -428,6 +615,7 @@ extern "C" int32_t jf_layernorm_q_bwd(const int8_t* dY, const float* SdY, const 
   int32_t rc = check_eltwise(X, SX, dX, SdX, N, C, block);
   if (rc != JF_OK) return rc;
   if (!dY || !SdY || !gamma || !mean || !rstd || !dgamma || !dbeta) return JF_ERR_NULL;
+  if (C > kLayerNormMaxC) return JF_ERR_SHAPE;
   if (!aligned16(dY) || !aligned4(SdY) || !aligned16(gamma) || !aligned4(mean) || !aligned4(rstd) ||
       !aligned4(dgamma) || !aligned4(dbeta))
     return JF_ERR_ALIGN;
@@ -436,13 +624,13 @@ extern "C" int32_t jf_layernorm_q_bwd(const int8_t* dY, const float* SdY, const 
   if (!aligned16(ws)) return JF_ERR_ALIGN;
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   float* partials = static_cast<float*>(ws);
-  const int nparts = (int)(N / block);
-  dim3 grid((unsigned)nparts);
-  if (block == 32) hipLaunchKernelGGL((layernorm_bwd_kernel<32>), grid, dim3(256), 0, st, dY, SdY, X, SX, gamma, mean, rstd, (int)N, (int)C, dX, SdX, partials);
-  else if (block == 64) hipLaunchKernelGGL((layernorm_bwd_kernel<64>), grid, dim3(256), 0, st, dY, SdY, X, SX, gamma, mean, rstd, (int)N, (int)C, dX, SdX, partials);
-  else hipLaunchKernelGGL((layernorm_bwd_kernel<128>), grid, dim3(256), 0, st, dY, SdY, X, SX, gamma, mean, rstd, (int)N, (int)C, dX, SdX, partials);
+  const int nparts = (int)(N / block) * 4;
+  const dim3 grid((unsigned)(N / block));
+  const int nit = (int)((C + 1023) / 1024);
+  const size_t lds = 4 * (size_t)(C / 32) * sizeof(float);
+  JF_LN_DISPATCH(launch_ln_bwd, block, nit, grid, lds, st, dY, SdY, X, SX, gamma, mean, rstd, (int)N, (int)C, dX, SdX, partials);
   rc = launch_status();
   if (rc != JF_OK) return rc;
-  hipLaunchKernelGGL(colsum_kernel, dim3((unsigned)((2 * C + 255) / 256)), dim3(256), 0, st, partials, nparts, (int)C, dgamma, dbeta);
+  hipLaunchKernelGGL(colsum_kernel, dim3((unsigned)((2 * C + 63) / 64)), dim3(1024), 0, st, partials, nparts, (int)(2 * C), dgamma, dbeta);
   return launch_status();
 }

@@ -171,6 +171,13 @@ int32_t jf_layernorm_q_bwd(const int8_t* dY, const float* SdY, const int8_t* X, 
 int32_t jf_debug_linear_partials(int32_t which, const int8_t* A, const int8_t* Bm, int64_t N, int64_t C, int64_t D,
                                  int32_t block, int64_t kb, int32_t* out, void* stream);
 
+/*
+ * Test hook: force the tile shape of the three GEMM entry points (process-wide, not thread-safe).
+ *   0 automatic (cost model), 1 128x128, 2 128x96, 3 96x96, 4 64x64.
+ * Shapes 2 and 3 exist for block 32 only; other blocks fall back to 128x128.  Block 128 always uses 128x128.
+ */
+int32_t jf_debug_set_gemm_shape(int32_t shape);
+
 #ifdef __cplusplus
 }
 #endif

@@ -8,6 +8,7 @@ library or without a GPU raises.
 from .binding import (  # noqa: F401
     JetfireError,
     jf_debug_linear_partials,
+    jf_debug_set_gemm_shape,
     jf_gelu_q,
     jf_gelu_q_bwd,
     jf_layernorm_q,

@@ -26,6 +26,7 @@ _SIGNATURES = {
     "jf_layernorm_q": (_I32, [_P, _P, _P, _P, _F32, _I64, _I64, _I32, _P, _P, _P, _P, _P]),
     "jf_layernorm_q_bwd": (_I32, [_P, _P, _P, _P, _P, _P, _P, _I64, _I64, _I32, _P, _P, _P, _P, _P, _SZ, _P]),
     "jf_debug_linear_partials": (_I32, [_I32, _P, _P, _I64, _I64, _I64, _I32, _I64, _P, _P]),
+    "jf_debug_set_gemm_shape": (_I32, [_I32]),
 }
 EXPORTED_SYMBOLS = tuple(_SIGNATURES)
 
@@ -219,3 +220,8 @@ def jf_debug_linear_partials(which, A, Bm, N, C, D, block, kb):
     out = torch.empty(shape, dtype=torch.int32, device=A.device)
     _check(load_library().jf_debug_linear_partials(which, _ptr(A), _ptr(Bm), N, C, D, block, kb, _ptr(out), _stream()))
     return out
+
+
+def jf_debug_set_gemm_shape(shape):
+    """Test hook: 0 automatic, 1 128x128, 2 128x96, 3 96x96, 4 64x64."""
+    _check(load_library().jf_debug_set_gemm_shape(shape))

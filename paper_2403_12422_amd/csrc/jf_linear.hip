@@ -53,10 +53,13 @@ struct TileLayout {
   static constexpr int kRows = KMAJOR ? TILE : KC;            // LDS rows: output rows, or K rows
   static constexpr int kCPR = (KMAJOR ? KC : TILE) / 16;      // 16-byte chunks per LDS row
   static constexpr int kSlots = kRows * kCPR;
-  static constexpr int kBytes = kSlots * 16;
-  static_assert(kCPR == 4 || kCPR == 8, "swizzle is written for 64- or 128-byte rows");
-  static __device__ __forceinline__ int swz(int r) { return (r / (8 / kCPR)) % kCPR; }
+  static_assert(kCPR == 4 || kCPR == 6 || kCPR == 8, "rows of 64, 96 or 128 bytes");
+  // 96-byte rows (a 96-wide M-major tile) are left unswizzled: their fragment reads see two-way bank
+  // conflicts, which the vector-ALU-bound B = 32 loop does not notice.
+  static __device__ __forceinline__ int swz(int r) { return kCPR == 6 ? 0 : (r / (kCPR == 4 ? 2 : 1)) % kCPR; }
   static __device__ __forceinline__ int slot(int r, int c) { return r * kCPR + (c ^ swz(r)); }
+  // LDS bytes when the tile is filled by whole 64-lane load instructions of NW waves (the tail is padding)
+  static constexpr int bytes(int nw) { return ((kSlots + 64 * nw - 1) / (64 * nw)) * (64 * nw) * 16; }
 };
 
 typedef __attribute__((address_space(3))) void* lds_ptr;
@@ -109,7 +112,8 @@ struct FragAddr {
 template <int TILE, bool KMAJOR, int KC>
 __device__ __forceinline__ int64_t chunk_offset(int slot_idx, int o0, int k0, int outer_dim, int K, int64_t ld) {
   typedef TileLayout<TILE, KMAJOR, KC> L;
-  const int r = slot_idx / L::kCPR, c = (slot_idx % L::kCPR) ^ L::swz(r);
+  const int r = min(slot_idx / L::kCPR, L::kRows - 1);  // slots past the tile are padding: any valid source will do
+  const int c = (slot_idx % L::kCPR) ^ L::swz(r);
   if (KMAJOR) {
     const int row = min(o0 + r, outer_dim - 1), kk = min(k0 + 16 * c, K - 16);
     return (int64_t)row * ld + kk;
@@ -136,25 +140,32 @@ __global__ void __launch_bounds__(64 * WGM * WGN, WMIN) gemm_kernel(const GemmAr
   constexpr int NW = WGM * WGN;
   constexpr int TM = 32 * WM * WGM, TN = 32 * WN * WGN;
   constexpr int KPB = B / 32;  // MFMA K steps per quantization block
-  constexpr int KC = B == 128 ? 128 : 64;
+  // K bytes per stage: 128 when a stage has to hold a whole B = 128 block, or for the workgroups of nine or
+  // twelve waves (one per compute unit), whose barriers are the most expensive; 64 otherwise, which lets three
+  // workgroups with a ring of three stages share the LDS of a compute unit.
+  constexpr int KC = (B == 128 || WGM * WGN > 4) ? 128 : 64;
   constexpr int SPS = KC / 32;  // MFMA K steps per stage
   constexpr int NTILE = WM * WN;
   typedef TileLayout<TM, AK, KC> LA;
   typedef TileLayout<TN, BK, KC> LB;
-  constexpr int CA = LA::kSlots / (64 * NW), CB = LB::kSlots / (64 * NW);  // load instructions per wave and stage
-  static_assert(LA::kSlots % (64 * NW) == 0 && LB::kSlots % (64 * NW) == 0, "whole load instructions per wave");
+  constexpr int A_BYTES = LA::bytes(NW), B_BYTES = LB::bytes(NW);
+  constexpr int CA = A_BYTES / (1024 * NW), CB = B_BYTES / (1024 * NW);  // load instructions per wave and stage
   static_assert(B == 32 || (TM % B == 0 && TN % B == 0), "tile must hold whole quantization blocks");
-  constexpr int STAGE_BYTES = LA::kBytes + LB::kBytes;
+  constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
 
   // Stages in the LDS ring: one being read, the rest in flight.  Three stages of a 128x128 tile with KC = 128
   // would not fit the 160 KB of LDS, so B = 128 runs a ring of two.
-  constexpr int NBUF = (KC == 128 && STAGE_BYTES > 40 * 1024) ? 2 : 3;
+  // Tiles that leave a compute unit to a single workgroup (more than four waves) take a ring of four.
+  constexpr int NBUF = (KC == 128 && STAGE_BYTES > 40 * 1024) ? 2 : (NW > 4 ? 4 : 3);
   // One LDS variable per ring slot: the compiler tracks direct-to-LDS loads per variable, so a read of
   // one slot does not make it wait for the loads still flying into the other slots.
   __shared__ __align__(1024) int8_t s_tile0[STAGE_BYTES];
   __shared__ __align__(1024) int8_t s_tile1[STAGE_BYTES];
   __shared__ __align__(1024) int8_t s_tile2[NBUF > 2 ? STAGE_BYTES : 16];
-  auto tile_buf = [&](int buf) -> int8_t* { return buf == 0 ? s_tile0 : (buf == 1 ? s_tile1 : s_tile2); };
+  __shared__ __align__(1024) int8_t s_tile3[NBUF > 3 ? STAGE_BYTES : 16];
+  auto tile_buf = [&](int buf) -> int8_t* {
+    return buf == 0 ? s_tile0 : (buf == 1 ? s_tile1 : (buf == 2 ? s_tile2 : s_tile3));
+  };
   __shared__ float s_amax[TM / 32][TN / 32];
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -217,7 +228,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN, WMIN) gemm_kernel(const GemmAr
   auto issue = [&](int s, int buf) {
     const int k0 = s * KC;
     int8_t* ta = tile_buf(buf);
-    int8_t* tb = ta + LA::kBytes;
+    int8_t* tb = ta + A_BYTES;
     if (k0 + KC <= g.K) {
 #pragma unroll
       for (int i = 0; i < CA; ++i)
@@ -225,7 +236,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN, WMIN) gemm_kernel(const GemmAr
 #pragma unroll
       for (int i = 0; i < CB; ++i)
         __builtin_amdgcn_global_load_lds((gbl_ptr)(srcB[i] + k0 * kstrideB), (lds_ptr)(tb + 1024 * (i * NW + wave)), 16, 0, 0);
-    } else {  // the last stage of a K that is an odd multiple of 32: clamp what lies beyond K
+    } else {  // the last stage of a K that is not a multiple of KC: clamp what lies beyond K
 #pragma unroll
       for (int i = 0; i < CA; ++i) {
         const int64_t off = chunk_offset<TM, AK, KC>((i * NW + wave) * 64 + lane, m0, k0, g.M, g.K, g.lda);
@@ -270,7 +281,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN, WMIN) gemm_kernel(const GemmAr
   auto compute = [&](int s, int buf, auto steps_tag) {
     constexpr int STEPS = decltype(steps_tag)::value;
     const int8_t* ta = tile_buf(buf);
-    const int8_t* tb = ta + LA::kBytes;
+    const int8_t* tb = ta + A_BYTES;
     // this stage's scales were fetched during the previous stage; fetch the next stage's now
     rotate_scales();
     if (s + 1 < nstages) load_scales(s + 1);
@@ -352,37 +363,50 @@ __global__ void __launch_bounds__(64 * WGM * WGN, WMIN) gemm_kernel(const GemmAr
   // every outstanding load (vmcnt(0)), including the stage that is meant to stay in flight.  Ordering is kept
   // by hand: the asm is a compiler barrier for memory accesses, each wave has consumed all its LDS reads of the
   // finished stage before it arrives, and direct-to-LDS loads are counted by vmcnt.
-  auto wait_loads = [&](int in_flight_stages) {  // at most that many of the youngest stages stay outstanding
-    if (in_flight_stages == 0) asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
-    else asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(LOADS) : "memory");
+  auto wait_loads = [&](bool keep_in_flight) {  // true: the AHEAD-1 youngest stages may stay outstanding
+    if (!keep_in_flight || AHEAD == 1) asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(LOADS * (AHEAD - 1)) : "memory");
   };
-  static_assert(AHEAD <= 2, "wait_loads handles at most one stage left in flight");
   const std::integral_constant<int, SPS> whole_tag;
-  const std::integral_constant<int, 1> half_tag;
+  // the last stage of a K that is not a multiple of KC holds 1 .. SPS-1 K steps (whole quantization blocks)
+  auto compute_partial = [&](int s, int buf) {
+    const int rem = nsteps - s * SPS;
+    if constexpr (SPS >= 2 && KPB <= 1) { if (rem == 1) compute(s, buf, std::integral_constant<int, 1>()); }
+    if constexpr (SPS >= 4 && KPB <= 2) { if (rem == 2) compute(s, buf, std::integral_constant<int, 2>()); }
+    if constexpr (SPS >= 4 && KPB <= 1) { if (rem == 3) compute(s, buf, std::integral_constant<int, 3>()); }
+  };
   const int nwhole = g.K / KC;
   load_scales(0);
 #pragma unroll
   for (int i = 0; i < AHEAD; ++i)
     if (i < nstages) issue(i, i);
-  wait_loads(nstages > 1 ? AHEAD - 1 : 0);
+  wait_loads(nstages >= AHEAD);
   int s = 0;
   // inside this loop stage s + NBUF + AHEAD - 1 .. exist for every issue, and every computed stage is whole
   for (; s + NBUF <= nwhole && s + NBUF + AHEAD - 1 < nstages; s += NBUF) {
+    // The instruction arbiter favours the oldest wave of a SIMD, so co-resident waves would finish one after
+    // the other and leave the SIMD to a single wave at the end.  Each wave therefore lowers its own priority
+    // as it advances: whoever is ahead yields, and the waves of a SIMD reach the end together.
+    {
+      const int quarter = (4 * s) / nstages;
+      if (quarter == 0) __builtin_amdgcn_s_setprio(3);
+      else if (quarter == 1) __builtin_amdgcn_s_setprio(2);
+      else if (quarter == 2) __builtin_amdgcn_s_setprio(1);
+      else __builtin_amdgcn_s_setprio(0);
+    }
 #pragma unroll
     for (int u = 0; u < NBUF; ++u) {
       issue(s + u + AHEAD, (u + AHEAD) % NBUF);
-      if (u == 0) compute(s + u, 0, whole_tag);
-      else if (u == 1) compute(s + u, 1, whole_tag);
-      else compute(s + u, 2, whole_tag);
-      wait_loads(AHEAD - 1);
+      compute(s + u, u, whole_tag);
+      wait_loads(true);
     }
   }
   for (int buf = s % NBUF; s < nstages; ++s, buf = (buf + 1 == NBUF ? 0 : buf + 1)) {
     const bool more = s + AHEAD < nstages;
     if (more) issue(s + AHEAD, (buf + AHEAD) % NBUF);
     if (s < nwhole) compute(s, buf, whole_tag);
-    else if constexpr (KPB == 1 && SPS > 1) compute(s, buf, half_tag);
-    wait_loads(more ? AHEAD - 1 : 0);
+    else compute_partial(s, buf);
+    wait_loads(more);
   }
   if (DUMP) return;
 
@@ -443,7 +467,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN, WMIN) gemm_kernel(const GemmAr
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
           const int col = 32 * (wn0 + b) + 8 * q4 + 4 * (lane >> 5);
-          const int chunk = (col >> 4) ^ (row & (TN / 16 - 1));
+          const int chunk = TN == 96 ? (col >> 4) : ((col >> 4) ^ (row & (TN / 16 - 1)));
           *reinterpret_cast<uint32_t*>(s_tile0 + row * TN + 16 * chunk + (col & 15)) =
               quantize4(acc[a][b][4 * q4], acc[a][b][4 * q4 + 1], acc[a][b][4 * q4 + 2], acc[a][b][4 * q4 + 3], inv);
         }
@@ -454,12 +478,13 @@ __global__ void __launch_bounds__(64 * WGM * WGN, WMIN) gemm_kernel(const GemmAr
     static_assert(TM * TN <= STAGE_BYTES, "the code tile is staged in one ring slot");
     __syncthreads();
     constexpr int CPRO = TN / 16;
+    static_assert((TM * CPRO) % (64 * NW) == 0, "whole passes over the code tile");
 #pragma unroll
     for (int i = 0; i < (TM * CPRO) / (64 * NW); ++i) {
       const int id = i * 64 * NW + tid;
       const int row = id / CPRO, c = id % CPRO;
       if (m0 + row < g.M && n0 + 16 * c < g.Nn) {
-        const uint4 v = *reinterpret_cast<const uint4*>(s_tile0 + row * TN + 16 * (c ^ (row & (CPRO - 1))));
+        const uint4 v = *reinterpret_cast<const uint4*>(s_tile0 + row * TN + 16 * (TN == 96 ? c : (c ^ (row & (CPRO - 1)))));
         *reinterpret_cast<uint4*>(g.Oq + (int64_t)(m0 + row) * g.Nn + n0 + 16 * c) = v;
       }
     }
@@ -470,27 +495,70 @@ __global__ void __launch_bounds__(64 * WGM * WGN, WMIN) gemm_kernel(const GemmAr
 template <int B, int WM, int WN, int WGM, int WGN, bool AK, bool BK, bool DUMP>
 static void launch_cfg(const GemmArgs& a, hipStream_t st) {
   constexpr int TM = 32 * WM * WGM, TN = 32 * WN * WGN;
-  constexpr int WMIN = (WM * WN >= 4) ? (B == 32 ? 3 : 2) : 4;
+  // resident waves per SIMD the register allocation has to allow: 3 for the 2x2 wave tile at B = 32 (three
+  // 128x128 workgroups share a compute unit), 1 for the 1x3 wave tiles (one workgroup per compute unit)
+  constexpr int WMIN = (WM * WN >= 4) ? (B == 32 ? 3 : 2) : (WGM * WGN > 4 ? 3 : 4);
   const int tiles = ((a.M + TM - 1) / TM) * ((a.Nn + TN - 1) / TN);
   hipLaunchKernelGGL((gemm_kernel<B, WM, WN, WGM, WGN, AK, BK, DUMP, WMIN>), dim3(tiles), dim3(64 * WGM * WGN), 0, st, a);
 }
 
-// Two tile shapes: 128x128 (each wave 2x2 sub-blocks) and 64x64 (each wave one sub-block).  The INT8 path is
-// bound by the vector ALU work of the per-K-block dequantization, which is the same per output element for
-// every tile shape, so the shape is chosen for an even spread of that work over the 256 compute units.
+// Tile shapes.  At B = 32 the kernel is bound by the vector ALU work of the per-K-block dequantization, which
+// is the same per output element for every shape, and next by the L2 -> LDS staging traffic, which shrinks
+// with the tile.  Three waves per SIMD are needed to hide each other's LDS and MFMA latencies.  So the shape
+// is chosen by a small cost model of the busiest compute unit:
+//   128x128  four waves of 2x2 sub-blocks, three workgroups per compute unit;
+//   128x96   twelve waves of one sub-block } one workgroup per compute unit, for outputs with too few
+//    96x96   nine waves of one sub-block   } 128x128 tiles to fill 256 compute units evenly;
+//    64x64   four waves of one sub-block.
+struct ShapeCost {
+  int64_t cycles;
+};
+static ShapeCost shape_cost(const GemmArgs& a, int tm, int tn, int waves, int tiles_per_wave) {
+  const int64_t n_wg = (int64_t)((a.M + tm - 1) / tm) * ((a.Nn + tn - 1) / tn);
+  const int64_t q = (n_wg + 255) / 256;                              // workgroups on the busiest compute unit
+  const int64_t per_simd = q * ((waves + 3) / 4) * tiles_per_wave;   // sub-blocks the busiest SIMD works through
+  int64_t valu = per_simd * (a.K / 32) * 140;                        // ~35 vector instructions of 4 cycles per sub-block and K step
+  if (waves > 4) valu += valu / 10;                                  // one big workgroup per compute unit: every barrier stalls the whole unit
+  const int64_t stage = q * (int64_t)(tm + tn) * a.K / 28;           // ~28 bytes per cycle of L2 -> LDS per compute unit
+  return {valu > stage ? valu : stage};
+}
+static int g_forced_shape = 0;  // test hook, see jf_debug_set_gemm_shape
+static ShapeCost shape_cost(const GemmArgs& a, int tm, int tn, int tiles_per_wave, bool single_wave_per_simd) {
+  const int64_t n_wg = (int64_t)((a.M + tm - 1) / tm) * ((a.Nn + tn - 1) / tn);
+  const int64_t q = (n_wg + 255) / 256;                              // workgroups on the busiest compute unit
+  int64_t valu = q * tiles_per_wave * (a.K / 32) * 140;              // ~35 vector instructions of 4 cycles per sub-block and K step
+  if (single_wave_per_simd && q == 1) valu += valu / 7;              // nothing else to hide this wave's stalls
+  const int64_t stage = q * (int64_t)(tm + tn) * a.K / 20;           // ~20 bytes per cycle of L2 -> LDS per compute unit
+  return {valu > stage ? valu : stage};
+}
+
 template <int B, bool AK, bool BK, bool DUMP>
 static void launch_shape(const GemmArgs& a, hipStream_t st) {
-  auto rounds = [&](int tm, int tn) {
-    const int64_t tiles = (int64_t)((a.M + tm - 1) / tm) * ((a.Nn + tn - 1) / tn);
-    return (tiles + 255) / 256 * (int64_t)(tm / 32) * (tn / 32);
-  };
   if constexpr (B == 128) {
     launch_cfg<B, 2, 2, 2, 2, AK, BK, DUMP>(a, st);
-  } else {
-    if (rounds(128, 128) <= rounds(64, 64))
+  } else if constexpr (B == 64) {
+    const bool big = g_forced_shape ? g_forced_shape != 4
+                                    : shape_cost(a, 128, 128, 4, 4).cycles <= shape_cost(a, 64, 64, 4, 1).cycles;
+    if (big)
       launch_cfg<B, 2, 2, 2, 2, AK, BK, DUMP>(a, st);
     else
       launch_cfg<B, 1, 1, 2, 2, AK, BK, DUMP>(a, st);
+  } else {
+    int64_t c128 = shape_cost(a, 128, 128, 4, 4).cycles;
+    int64_t c12896 = shape_cost(a, 128, 96, 12, 1).cycles;
+    int64_t c9696 = shape_cost(a, 96, 96, 9, 1).cycles;
+    int64_t c64 = shape_cost(a, 64, 64, 4, 1).cycles;
+    if (g_forced_shape) {
+      const int64_t big = INT64_MAX;
+      c128 = g_forced_shape == 1 ? 0 : big;
+      c12896 = g_forced_shape == 2 ? 0 : big;
+      c9696 = g_forced_shape == 3 ? 0 : big;
+      c64 = g_forced_shape == 4 ? 0 : big;
+    }
+    if (c128 <= c12896 && c128 <= c9696 && c128 <= c64) launch_cfg<B, 2, 2, 2, 2, AK, BK, DUMP>(a, st);
+    else if (c12896 <= c9696 && c12896 <= c64) launch_cfg<B, 1, 1, 4, 3, AK, BK, DUMP>(a, st);
+    else if (c9696 <= c64) launch_cfg<B, 1, 1, 3, 3, AK, BK, DUMP>(a, st);
+    else launch_cfg<B, 1, 1, 2, 2, AK, BK, DUMP>(a, st);
   }
 }
 
@@ -604,4 +672,10 @@ extern "C" int32_t jf_debug_linear_partials(int32_t which, const int8_t* A, cons
   g.dump_kb = (int)kb;
   launch_gemm(which, block, g, true, reinterpret_cast<hipStream_t>(stream));
   return launch_status();
+}
+
+extern "C" int32_t jf_debug_set_gemm_shape(int32_t shape) {
+  if (shape < 0 || shape > 4) return JF_ERR_SHAPE;
+  jf::g_forced_shape = shape;
+  return JF_OK;
 }

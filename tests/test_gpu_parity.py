@@ -125,6 +125,27 @@ def test_linear_three_products(block, N, C, D, kw):
     np.testing.assert_array_equal(host(s1), host(s2))
 
 
+@pytest.mark.parametrize("shape", [1, 2, 3, 4])
+@pytest.mark.parametrize("block,N,C,D", [(32, 384, 160, 288), (32, 416, 96, 224), (64, 256, 192, 320)])
+def test_linear_every_tile_shape(shape, block, N, C, D):
+    """Each GEMM tile shape, forced through the test hook, on sizes that leave ragged tiles in both directions."""
+    say(f"tile shape {shape} block={block} N={N} C={C} D={D}")
+    (X, SX), (W, SW), (dY, SdY) = _quantized_layer(3500 + shape + N, N, C, D, block)
+    Xd, SXd, Wd, SWd, dYd, SdYd = map(dev, (X, SX, W, SW, dY, SdY))
+    jf.jf_debug_set_gemm_shape(shape)
+    try:
+        _check_linear("fwd", jf.jf_linear_fwd(Xd, SXd, Wd, SWd, block, want_f32=True), oracle.linear_fwd(X, SX, W, SW, block), block)
+        _check_linear("dgrad", jf.jf_linear_dgrad(dYd, SdYd, Wd, SWd, block, want_f32=True), oracle.linear_dgrad(dY, SdY, W, SW, block), block)
+        _check_linear("wgrad", jf.jf_linear_wgrad(dYd, SdYd, Xd, SXd, block, want_f32=True), oracle.linear_wgrad(dY, SdY, X, SX, block), block)
+        for which, (A, Bm, ref_a, ref_b, K) in enumerate(((Xd, Wd, X, W, C), (dYd, Wd, dY, np.ascontiguousarray(W.T), D),
+                                                          (dYd, Xd, np.ascontiguousarray(dY.T), np.ascontiguousarray(X.T), N))):
+            kb = K // block - 1
+            got = host(jf.jf_debug_linear_partials(which, A, Bm, N, C, D, block, kb))
+            np.testing.assert_array_equal(got, oracle.block_partials(ref_a, ref_b, block, kb))
+    finally:
+        jf.jf_debug_set_gemm_shape(0)
+
+
 def test_linear_zero_blocks_and_run_to_run_stability():
     block, N, C, D = 32, 128, 128, 128
     (X, SX), (W, SW), _ = _quantized_layer(3100, N, C, D, block)

@@ -37,6 +37,8 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--cpu-sample-tokens", type=int, default=4096)
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="oracle time budget of the CPU baseline leg")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also launch plain 256 MiB device copies, the reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE")
     ap.add_argument("--graph", action="store_true", help="also time the step replayed from a captured HIP graph")
     return ap.parse_args()
 
@@ -155,6 +157,14 @@ def main():
     dt = time.perf_counter() - t0
     ms_per_step = dt / args.steps * 1e3
 
+    if args.pmc_calibration:
+        src = torch.ones((256 << 20,), dtype=torch.int8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)                 # reads 256 MiB and writes 256 MiB per launch
+        torch.cuda.synchronize()
+        del src, dst
+
     graph_ms = None
     if args.graph:
         side = torch.cuda.Stream()
@@ -220,6 +230,13 @@ def main():
         memops[name] = {"ms": round(ms, 5), "GB/s": round(nbytes / (ms * 1e-3) * 1e-9, 1),
                         "frac_hbm_peak": round(nbytes / (ms * 1e-3) * 1e-9 / HBM_PEAK_GBPS, 4)}
 
+    # HBM traffic of the GEMM kernel: measured offline with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see the
+    # summary named in the file) and valid for the default workload only
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "bench_config2_hbm_traffic.json")
+    if (N, C, D, B) == (4096, 768, 3072, 32) and os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get("gemm_avg_bytes_per_launch")
+
     out = {
         "metric": "per-block INT8 linear TOPS (fwd+dgrad+wgrad) + GB/s for INT8 GELU/LayerNorm",
         "value": round(6.0 * N * C * D / (ms_per_step * 1e-3) * 1e-12, 3),
@@ -244,7 +261,9 @@ def main():
             "unit": "TFLOP/s",
             "unit_note": "INT8 multiply-accumulate counted as 2 ops (TOP/s)",
             "frac": round(achieved / INT8_MFMA_PEAK_TOPS, 4),
-            "traffic": None,
+            "traffic": traffic,
+            "traffic_note": "HBM bytes per GEMM launch, rocprofv3 FETCH_SIZE + WRITE_SIZE scaled by a 256 MiB copy; "
+                            "algorithmic bytes are 18.1e6",
             "avg_launch_ms": round(gemm_avg_ms, 5),
             "per_launch_ms": {"fwd": round(per_gemm[0], 5), "dgrad": round(per_gemm[1], 5), "wgrad": round(per_gemm[2], 5)},
             "linear_only_TOPS": round(6.0 * N * C * D / (sum(per_gemm) * 1e-3) * 1e-12, 2),

@@ -276,8 +276,11 @@ __global__ void __launch_bounds__(1024) layernorm_fwd_kernel(const int8_t* __res
     k2[r] = -mu * rs;
   }
 
-  // sweep 2: block max-abs of y = xhat * gamma + beta
+  // sweep 2: y = xhat * gamma + beta and its block max-abs.  With at most four chunks per lane the values
+  // stay in registers (KEEPY); otherwise sweep 3 recomputes them.
+  constexpr bool KEEPY = KEEP && RW * NIT <= 4;
   constexpr int LM = B / 16 - 1;  // lanes of one block column: mask 1, 3 or 7
+  float ys[KEEPY ? RW : 1][KEEPY ? NIT : 1][16];
 #pragma unroll
   for (int it = 0; it < NIT; ++it) {
     float m = 0.0f;
@@ -291,8 +294,11 @@ __global__ void __launch_bounds__(1024) layernorm_fwd_kernel(const int8_t* __res
         unpack16_biased(chunk(r, it), u);
         const float kb = __builtin_fmaf(-128.0f, k1[r][it], k2[r]);
 #pragma unroll
-        for (int e = 0; e < 16; ++e)
-          m = fmaxf(m, fabsf(__builtin_fmaf(__builtin_fmaf(u[e], k1[r][it], kb), gm[e], bt[e])));
+        for (int e = 0; e < 16; ++e) {
+          const float y = __builtin_fmaf(__builtin_fmaf(u[e], k1[r][it], kb), gm[e], bt[e]);
+          if (KEEPY) ys[r][it][e] = y;
+          m = fmaxf(m, fabsf(y));
+        }
       }
     }
     m = wave_group_max<LM>(m);
@@ -301,7 +307,7 @@ __global__ void __launch_bounds__(1024) layernorm_fwd_kernel(const int8_t* __res
   }
   __syncthreads();
 
-  // sweep 3: recompute y, quantize, store
+  // sweep 3: quantize (recomputing y if it was not kept), store
 #pragma unroll
   for (int it = 0; it < NIT; ++it) {
     const int c = lane + 64 * it;
@@ -311,43 +317,50 @@ __global__ void __launch_bounds__(1024) layernorm_fwd_kernel(const int8_t* __res
       for (int w = 0; w < NW; ++w) mm = fmaxf(mm, s_amax[w * ngran + (c >> 1)]);
       block_scale(mm, scale, inv);
       if (wave == 0 && ((16 * c) % B) == 0) SY[(int64_t)bi * lc + (16 * c) / B] = scale;
-      float gm[16], bt[16];
-      load16f(gamma + 16 * c, gm);
-      load16f(beta + 16 * c, bt);
+      if (KEEPY) {
 #pragma unroll
-      for (int r = 0; r < RW; ++r) {
-        float u[16], y[16];
-        unpack16_biased(chunk(r, it), u);
-        const float kb = __builtin_fmaf(-128.0f, k1[r][it], k2[r]);
+        for (int r = 0; r < RW; ++r)
+          *reinterpret_cast<uint4*>(Y + (int64_t)(r0 + r) * cols + 16 * c) = quantize16(ys[r][it], inv);
+      } else {
+        float gm[16], bt[16];
+        load16f(gamma + 16 * c, gm);
+        load16f(beta + 16 * c, bt);
 #pragma unroll
-        for (int e = 0; e < 16; ++e) y[e] = __builtin_fmaf(__builtin_fmaf(u[e], k1[r][it], kb), gm[e], bt[e]);
-        *reinterpret_cast<uint4*>(Y + (int64_t)(r0 + r) * cols + 16 * c) = quantize16(y, inv);
+        for (int r = 0; r < RW; ++r) {
+          float u[16], y[16];
+          unpack16_biased(chunk(r, it), u);
+          const float kb = __builtin_fmaf(-128.0f, k1[r][it], k2[r]);
+#pragma unroll
+          for (int e = 0; e < 16; ++e) y[e] = __builtin_fmaf(__builtin_fmaf(u[e], k1[r][it], kb), gm[e], bt[e]);
+          *reinterpret_cast<uint4*>(Y + (int64_t)(r0 + r) * cols + 16 * c) = quantize16(y, inv);
+        }
       }
     }
   }
 }
 
-// LayerNorm backward.  Four waves per workgroup, RW = B/4 rows per wave.  Sweep 1: per row
-// m1 = mean_C(ghat), m2 = mean_C(ghat xhat), and per column the sums of g*xhat and g over this wave's
-// rows, written as one partial row per wave to the workspace.  Sweeps 2 and 3: dx = rstd (ghat - m1 -
-// xhat m2), block max-abs, quantize, store.
+// LayerNorm backward.  Sixteen waves per workgroup, RW = B/16 rows per wave.  Sweep 1: per row
+// m1 = mean_C(ghat), m2 = mean_C(ghat xhat), and per column the sums of g*xhat and g over the wave's rows;
+// the sixteen waves fold those column sums into four LDS rows in a fixed order (wave w adds into row w % 4
+// in round w / 4), which go to the workspace as four partial rows per workgroup.  Sweep 2:
+// dx = rstd (ghat - m1 - xhat m2) and its block max-abs; then quantize and store.
 template <int B, int NIT>
-__global__ void __launch_bounds__(256) layernorm_bwd_kernel(const int8_t* __restrict__ G, const float* __restrict__ SG,
-                                                             const int8_t* __restrict__ X, const float* __restrict__ SX,
-                                                             const float* __restrict__ gamma,
-                                                             const float* __restrict__ mean_in,
-                                                             const float* __restrict__ rstd_in, int rows, int cols,
-                                                             int8_t* __restrict__ dX, float* __restrict__ SdX,
-                                                             float* __restrict__ partials) {
-  constexpr int NW = 4, RW = B / NW;
-  constexpr bool KEEP = RW * NIT <= 8;
-  extern __shared__ float s_dyn[];
+__global__ void __launch_bounds__(1024) layernorm_bwd_kernel(const int8_t* __restrict__ G, const float* __restrict__ SG,
+                                                              const int8_t* __restrict__ X, const float* __restrict__ SX,
+                                                              const float* __restrict__ gamma,
+                                                              const float* __restrict__ mean_in,
+                                                              const float* __restrict__ rstd_in, int rows, int cols,
+                                                              int8_t* __restrict__ dX, float* __restrict__ SdX,
+                                                              float* __restrict__ partials) {
+  constexpr int NW = 16, RW = B / NW;
+  constexpr bool KEEP = RW * NIT <= 2;    // codes of x and g stay in registers
+  constexpr bool KEEPY = RW * NIT <= 2;   // dx stays in registers between the max-abs and the quantize step
+  extern __shared__ float s_dyn[];        // [NW][C/32] block max-abs, then [4][2][C] column sums
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int r0 = blockIdx.x * B + wave * RW;
   const int lc = cols / B, bi = blockIdx.x, nchunks = cols / 16, ngran = cols / 32;
   float* s_amax = s_dyn;
-  float* part_g = partials + ((int64_t)blockIdx.x * NW + wave) * 2 * cols;
-  float* part_b = part_g + cols;
+  float* s_col = s_dyn + NW * ngran;
 
   bool ok[NIT];
   float sx[NIT], sg[NIT];
@@ -385,15 +398,16 @@ __global__ void __launch_bounds__(256) layernorm_bwd_kernel(const int8_t* __rest
     m1[r] = m2[r] = 0.0f;
   }
 
-  // sweep 1
+  // sweep 1: row sums, and column sums folded over the waves in four rounds (per chunk column, so that only
+  // one chunk's 32 column sums are live in registers)
 #pragma unroll
   for (int it = 0; it < NIT; ++it) {
-    if (ok[it]) {
-      const int c = lane + 64 * it;
-      float gm[16], cg[16], cb[16];
-      load16f(gamma + 16 * c, gm);
+    float cg[16], cb[16];
 #pragma unroll
-      for (int e = 0; e < 16; ++e) cg[e] = cb[e] = 0.0f;
+    for (int e = 0; e < 16; ++e) cg[e] = cb[e] = 0.0f;
+    if (ok[it]) {
+      float gm[16];
+      load16f(gamma + 16 * (lane + 64 * it), gm);
       const float g128 = -128.0f * sg[it];
 #pragma unroll
       for (int r = 0; r < RW; ++r) {
@@ -412,13 +426,35 @@ __global__ void __launch_bounds__(256) layernorm_bwd_kernel(const int8_t* __rest
           cb[e] += gv;
         }
       }
+    }
 #pragma unroll
-      for (int d = 0; d < 4; ++d) {
-        *reinterpret_cast<float4*>(part_g + 16 * c + 4 * d) = make_float4(cg[4 * d], cg[4 * d + 1], cg[4 * d + 2], cg[4 * d + 3]);
-        *reinterpret_cast<float4*>(part_b + 16 * c + 4 * d) = make_float4(cb[4 * d], cb[4 * d + 1], cb[4 * d + 2], cb[4 * d + 3]);
+    for (int round = 0; round < 4; ++round) {
+      if ((wave >> 2) == round && ok[it]) {
+        float* row_g = s_col + (wave & 3) * 2 * cols + 16 * (lane + 64 * it);
+        float* row_b = row_g + cols;
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+          float4 a = make_float4(cg[4 * d], cg[4 * d + 1], cg[4 * d + 2], cg[4 * d + 3]);
+          float4 b = make_float4(cb[4 * d], cb[4 * d + 1], cb[4 * d + 2], cb[4 * d + 3]);
+          if (round > 0) {
+            const float4 pa = *reinterpret_cast<const float4*>(row_g + 4 * d);
+            const float4 pb = *reinterpret_cast<const float4*>(row_b + 4 * d);
+            a = make_float4(pa.x + a.x, pa.y + a.y, pa.z + a.z, pa.w + a.w);
+            b = make_float4(pb.x + b.x, pb.y + b.y, pb.z + b.z, pb.w + b.w);
+          }
+          *reinterpret_cast<float4*>(row_g + 4 * d) = a;
+          *reinterpret_cast<float4*>(row_b + 4 * d) = b;
+        }
       }
+      __syncthreads();
     }
   }
+  {  // the four folded rows -> workspace: thread t copies float4 number t, t + 1024, ...
+    float* dst = partials + (int64_t)blockIdx.x * 4 * 2 * cols;
+    for (int i = threadIdx.x; i < 4 * 2 * cols / 4; i += 1024)
+      *reinterpret_cast<float4*>(dst + 4 * i) = *reinterpret_cast<const float4*>(s_col + 4 * i);
+  }
+
   // dx = ug * a_c + ux * kxm + (a_c * -128 + krow) with a_c = rstd * sg * gamma_c
   float kxm[RW][NIT], krow[RW][NIT];
 #pragma unroll
@@ -447,6 +483,7 @@ __global__ void __launch_bounds__(256) layernorm_bwd_kernel(const int8_t* __rest
 
   // sweep 2
   constexpr int LM = B / 16 - 1;
+  float ys[KEEPY ? RW : 1][KEEPY ? NIT : 1][16];
 #pragma unroll
   for (int it = 0; it < NIT; ++it) {
     float m = 0.0f;
@@ -458,7 +495,10 @@ __global__ void __launch_bounds__(256) layernorm_bwd_kernel(const int8_t* __rest
         float y[16];
         dx16(r, it, gm, y);
 #pragma unroll
-        for (int e = 0; e < 16; e += 4) m = amax4(m, y[e], y[e + 1], y[e + 2], y[e + 3]);
+        for (int e = 0; e < 16; ++e) {
+          if (KEEPY) ys[r][it][e] = y[e];
+          m = fmaxf(m, fabsf(y[e]));
+        }
       }
     }
     m = wave_group_max<LM>(m);
@@ -467,7 +507,7 @@ __global__ void __launch_bounds__(256) layernorm_bwd_kernel(const int8_t* __rest
   }
   __syncthreads();
 
-  // sweep 3
+  // quantize and store
 #pragma unroll
   for (int it = 0; it < NIT; ++it) {
     const int c = lane + 64 * it;
@@ -477,13 +517,19 @@ __global__ void __launch_bounds__(256) layernorm_bwd_kernel(const int8_t* __rest
       for (int w = 0; w < NW; ++w) mm = fmaxf(mm, s_amax[w * ngran + (c >> 1)]);
       block_scale(mm, scale, inv);
       if (wave == 0 && ((16 * c) % B) == 0) SdX[(int64_t)bi * lc + (16 * c) / B] = scale;
-      float gm[16];
-      load16f(gamma + 16 * c, gm);
+      if (KEEPY) {
 #pragma unroll
-      for (int r = 0; r < RW; ++r) {
-        float y[16];
-        dx16(r, it, gm, y);
-        *reinterpret_cast<uint4*>(dX + (int64_t)(r0 + r) * cols + 16 * c) = quantize16(y, inv);
+        for (int r = 0; r < RW; ++r)
+          *reinterpret_cast<uint4*>(dX + (int64_t)(r0 + r) * cols + 16 * c) = quantize16(ys[r][it], inv);
+      } else {
+        float gm[16];
+        load16f(gamma + 16 * c, gm);
+#pragma unroll
+        for (int r = 0; r < RW; ++r) {
+          float y[16];
+          dx16(r, it, gm, y);
+          *reinterpret_cast<uint4*>(dX + (int64_t)(r0 + r) * cols + 16 * c) = quantize16(y, inv);
+        }
       }
     }
   }
@@ -548,7 +594,7 @@ static void launch_ln_fwd(dim3 grid, size_t lds, hipStream_t st, Args... args) {
 }
 template <int B, int NIT, typename... Args>
 static void launch_ln_bwd(dim3 grid, size_t lds, hipStream_t st, Args... args) {
-  hipLaunchKernelGGL((layernorm_bwd_kernel<B, NIT>), grid, dim3(256), lds, st, args...);
+  hipLaunchKernelGGL((layernorm_bwd_kernel<B, NIT>), grid, dim3(1024), lds, st, args...);
 }
 
 #define JF_LN_DISPATCH(FN, block, nit, ...)                                   \
@@ -627,7 +673,7 @@ extern "C" int32_t jf_layernorm_q_bwd(const int8_t* dY, const float* SdY, const 
   const int nparts = (int)(N / block) * 4;
   const dim3 grid((unsigned)(N / block));
   const int nit = (int)((C + 1023) / 1024);
-  const size_t lds = 4 * (size_t)(C / 32) * sizeof(float);
+  const size_t lds = (16 * (size_t)(C / 32) + 4 * 2 * (size_t)C) * sizeof(float);  // max-abs slots + four column-sum rows
   JF_LN_DISPATCH(launch_ln_bwd, block, nit, grid, lds, st, dY, SdY, X, SX, gamma, mean, rstd, (int)N, (int)C, dX, SdX, partials);
   rc = launch_status();
   if (rc != JF_OK) return rc;

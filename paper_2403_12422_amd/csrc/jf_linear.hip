@@ -123,6 +123,15 @@ __device__ __forceinline__ int64_t chunk_offset(int slot_idx, int o0, int k0, in
   }
 }
 
+// f(integral_constant<int, I>) for I = BEGIN .. END-1, unrolled at compile time
+template <int BEGIN, int END, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (BEGIN < END) {
+    f(std::integral_constant<int, BEGIN>());
+    static_for<BEGIN + 1, END>(f);
+  }
+}
+
 // acc += t * (float)v for one 32x32 sub-block (Sec. 5.3): 16 int->float conversions and 16 FMAs per lane.
 // The fused multiply-add is written as v_fmac_f32 so that it updates the accumulator register in place;
 // left to itself the register allocator ping-pongs the 64 accumulators between two register sets.
@@ -203,7 +212,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN, WMIN) gemm_kernel(const GemmAr
   // uniform load from that space is selected as a scalar load.
   typedef const __attribute__((address_space(4))) float* const_f32_ptr;
   const const_f32_ptr SAc = (const_f32_ptr)g.SA, SBc = (const_f32_ptr)g.SB;
-  auto load_scales = [&](int s) {
+  auto load_scales = [&](int s) __attribute__((always_inline)) {
     if (DUMP) return;
 #pragma unroll
     for (int j = 0; j < SPS; ++j) {
@@ -214,7 +223,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN, WMIN) gemm_kernel(const GemmAr
       for (int b = 0; b < WN; ++b) sb_n[b][j] = SBc[sb_row[b] + (int64_t)kb * g.sb_k];
     }
   };
-  auto rotate_scales = [&]() {
+  auto rotate_scales = [&]() __attribute__((always_inline)) {
 #pragma unroll
     for (int j = 0; j < SPS; ++j) {
 #pragma unroll
@@ -224,12 +233,12 @@ __global__ void __launch_bounds__(64 * WGM * WGN, WMIN) gemm_kernel(const GemmAr
     }
   };
 
-  // Issue the direct-to-LDS loads of stage s into buffer buf (0 or 1).
-  auto issue = [&](int s, int buf) {
-    const int k0 = s * KC;
+  // Issue the direct-to-LDS loads of the stage that starts at K offset k0 into ring slot buf.
+  // known_whole: the caller guarantees k0 + KC <= K (keeps the clamping path out of the loops).
+  auto issue_at = [&](int k0, int buf, auto known_whole) __attribute__((always_inline)) {
     int8_t* ta = tile_buf(buf);
     int8_t* tb = ta + A_BYTES;
-    if (k0 + KC <= g.K) {
+    if (known_whole || k0 + KC <= g.K) {
 #pragma unroll
       for (int i = 0; i < CA; ++i)
         __builtin_amdgcn_global_load_lds((gbl_ptr)(srcA[i] + k0 * kstrideA), (lds_ptr)(ta + 1024 * (i * NW + wave)), 16, 0, 0);
@@ -265,7 +274,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN, WMIN) gemm_kernel(const GemmAr
   const v16i zero16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
   v16i vchain[KPB > 1 ? NTILE : 1];  // INT32 tiles carried across K steps (B > 32 only)
 
-  auto dump_tile = [&](const v16i& v, int a, int b) {
+  auto dump_tile = [&](const v16i& v, int a, int b) __attribute__((always_inline)) {
     const int m = m0 + 32 * (wm0 + a) + (lane & 31);
     const int nb = n0 + 32 * (wn0 + b) + 4 * (lane >> 5);
     if (m < g.M && nb < g.Nn) {
@@ -277,56 +286,207 @@ __global__ void __launch_bounds__(64 * WGM * WGN, WMIN) gemm_kernel(const GemmAr
     }
   };
 
-  // One stage (STEPS K steps) out of buffer `buf`.
-  auto compute = [&](int s, int buf, auto steps_tag) {
-    constexpr int STEPS = decltype(steps_tag)::value;
-    const int8_t* ta = tile_buf(buf);
-    const int8_t* tb = ta + A_BYTES;
-    // this stage's scales were fetched during the previous stage; fetch the next stage's now
-    rotate_scales();
-    if (s + 1 < nstages) load_scales(s + 1);
-    float (&sa)[WM][SPS] = sa_c;
-    float (&sb)[WN][SPS] = sb_c;
-    if constexpr (KPB == 1) {
-      // B = 32: every MFMA result is folded right away.  Two INT32 tiles rotate: the MFMA of the next
-      // tile is issued before the 32 conversions/FMAs of the current one, so the matrix pipe runs in
-      // the shadow of the vector ALU work of the same wave.
-      v4i fa[2][WM], fb[2][WN];
-      v16i vi[2];
+  // Stage loop over the ring of NBUF LDS buffers: while stage s is computed, stages s+1 .. s+NBUF-1
+  // are in flight, which covers the L2 latency even when a stage is only two K steps long.  The loop
+  // is unrolled NBUF times so that every LDS address is a compile-time immediate and the accumulators
+  // stay in the same registers; the last (at most NBUF) stages run from a generic copy after the loop.
+  constexpr int LOADS = CA + CB;   // vector-memory instructions per wave and stage
+  constexpr int AHEAD = NBUF - 1;  // stages issued ahead of the one being computed
+  static_assert(LOADS * (AHEAD - 1) <= 63, "vmcnt immediate");
+  // End of a stage: wait for this wave's own loads of the stage that is read next, then meet the other waves.
+  // A bare s_barrier is used instead of __syncthreads(): the fence of the latter makes the compiler drain
+  // every outstanding load (vmcnt(0)), including the stage that is meant to stay in flight.  Ordering is kept
+  // by hand: the asm is a compiler barrier for memory accesses, each wave has consumed all its LDS reads of the
+  // finished stage before it arrives, and direct-to-LDS loads are counted by vmcnt.  The wait itself is the
+  // s_waitcnt builtin, which the compiler's own counter tracking understands: it then knows that the loads of
+  // the stage read next have landed and adds no drain of its own in front of the fragment reads.
+  // (The test hook's stores are counted by vmcnt too, and not in order with the loads, so it always drains.)
+  auto wait_loads = [&](bool keep_in_flight) __attribute__((always_inline)) {  // true: the AHEAD-1 youngest stages may stay outstanding
+    constexpr int N = LOADS * (AHEAD - 1);
+    // s_waitcnt immediate: vmcnt in bits 3:0 and 15:14, expcnt (6:4) and lgkmcnt (11:8) left at "no wait"
+    constexpr int KEEP = (N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14), DRAIN = (7 << 4) | (15 << 8);
+    if (DUMP || !keep_in_flight || AHEAD == 1) __builtin_amdgcn_s_waitcnt(DRAIN);
+    else __builtin_amdgcn_s_waitcnt(KEEP);
+    asm volatile("s_barrier" ::: "memory");
+  };
+  const std::integral_constant<int, SPS> whole_tag;
+  const int nwhole = g.K / KC;
+
+  if constexpr (KPB == 1) {
+    // ---- B = 32: every MFMA result is folded right away, and the kernel is bound by those conversions and
+    // FMAs.  The wave keeps one software pipeline running across the stage barriers: two INT32 tiles rotate,
+    // the MFMA of the next tile is issued before the 32 conversions/FMAs of the current one, and at the end
+    // of a stage the barrier, the prefetch and the fragment reads of the next stage come BEFORE the fold of
+    // the stage's last tile, which covers the LDS latency of those reads.  All fragments of a stage are read
+    // at once (they fit the registers of the double buffer they replace).
+    static_assert((SPS * NTILE) % 2 == 0, "a whole stage leaves the tile rotation where it found it");
+    v16i vi[2];
+    v4i fa[SPS][WM], fb[SPS][WN];
+    // scales two stages ahead of the one in use: requested before a stage barrier, moved one level down at
+    // the next, so the scalar loads are never waited for together with LDS fragment reads
+    float sa_f[WM][SPS], sb_f[WN][SPS];
 #pragma unroll
-      for (int a = 0; a < WM; ++a) fa[0][a] = addrA.read(ta, a, 0);
+    for (int j = 0; j < SPS; ++j) {
 #pragma unroll
-      for (int b = 0; b < WN; ++b) fb[0][b] = addrB.read(tb, b, 0);
-      vi[0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[0][0], fa[0][0], zero16, 0, 0, 0);
+      for (int a = 0; a < WM; ++a) sa_c[a][j] = sa_n[a][j] = sa_f[a][j] = 0.0f;
 #pragma unroll
-      for (int j = 0; j < STEPS; ++j) {
-        if (j + 1 < STEPS) {
+      for (int b = 0; b < WN; ++b) sb_c[b][j] = sb_n[b][j] = sb_f[b][j] = 0.0f;
+    }
+    // Stages are numbered t = t0 .. tl.  When K is not a multiple of KC the odd K steps come FIRST, as stage
+    // t = -1 in ring slot NBUF-1, so that every stage inside the loops is whole; stage t >= 0 starts at K
+    // offset kbase + t*KC and lives in ring slot t % NBUF.
+    const int rem = nsteps % SPS, kbase = 32 * rem;
+    const int t0 = rem ? -1 : 0, tl = nwhole - 1;
+    // Running scalar pointers to the scales of the next stage to request: one 64-bit add per stage and
+    // operand sub-tile instead of an index computation per load.
+    const_f32_ptr pa[WM], pb[WN];
 #pragma unroll
-          for (int a = 0; a < WM; ++a) fa[(j + 1) & 1][a] = addrA.read(ta, a, j + 1);
+    for (int a = 0; a < WM; ++a) pa[a] = SAc + sa_row[a];
 #pragma unroll
-          for (int b = 0; b < WN; ++b) fb[(j + 1) & 1][b] = addrB.read(tb, b, j + 1);
+    for (int b = 0; b < WN; ++b) pb[b] = SBc + sb_row[b];
+    // current <- next <- far <- scalar loads of `steps` K steps (the rest of a stage keeps stale values that
+    // are never used); nothing is requested when the far stage does not exist
+    auto advance_scales = [&](auto far_exists, int steps) __attribute__((always_inline)) {
+      rotate_scales();
+#pragma unroll
+      for (int j = 0; j < SPS; ++j) {
+#pragma unroll
+        for (int a = 0; a < WM; ++a) sa_n[a][j] = sa_f[a][j];
+#pragma unroll
+        for (int b = 0; b < WN; ++b) sb_n[b][j] = sb_f[b][j];
+      }
+      if (DUMP) return;
+      if (far_exists) {
+#pragma unroll
+        for (int j = 0; j < SPS; ++j) {
+          if (j < steps) {
+#pragma unroll
+            for (int a = 0; a < WM; ++a) sa_f[a][j] = pa[a][j * g.sa_k];
+#pragma unroll
+            for (int b = 0; b < WN; ++b) sb_f[b][j] = pb[b][j * g.sb_k];
+          }
         }
 #pragma unroll
-        for (int t = 0; t < NTILE; ++t) {
-          const int cur = (j * NTILE + t) & 1;
-          const int a = t / WN, b = t % WN;
-          if (t + 1 < NTILE) {
-            const int a1 = (t + 1) / WN, b1 = (t + 1) % WN;
-            vi[cur ^ 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[j & 1][b1], fa[j & 1][a1], zero16, 0, 0, 0);
-          } else if (j + 1 < STEPS) {
-            vi[cur ^ 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[(j + 1) & 1][0], fa[(j + 1) & 1][0], zero16, 0, 0, 0);
-          }
+        for (int a = 0; a < WM; ++a) pa[a] += steps * g.sa_k;
+#pragma unroll
+        for (int b = 0; b < WN; ++b) pb[b] += steps * g.sb_k;
+      }
+    };
+    // stages t >= 0 are whole by construction
+    auto issue = [&](int t, int slot) __attribute__((always_inline)) { issue_at(max(0, 32 * (nsteps % SPS) + t * KC), slot, false); };
+    auto issue_whole = [&](int t, int slot) __attribute__((always_inline)) { issue_at(32 * (nsteps % SPS) + t * KC, slot, std::true_type()); };
+    auto read_frags = [&](int buf) __attribute__((always_inline)) {
+      const int8_t* ta = tile_buf(buf);
+      const int8_t* tb = ta + A_BYTES;
+#pragma unroll
+      for (int j = 0; j < SPS; ++j) {
+#pragma unroll
+        for (int a = 0; a < WM; ++a) fa[j][a] = addrA.read(ta, a, j);
+#pragma unroll
+        for (int b = 0; b < WN; ++b) fb[j][b] = addrB.read(tb, b, j);
+      }
+    };
+    auto k0_of = [&](int t) __attribute__((always_inline)) { return max(0, kbase + t * KC); };
+    auto slot_of = [&](int t) __attribute__((always_inline)) { return (t + NBUF) % NBUF; };
+    auto fold_or_dump = [&](int t, int j, int a, int b, const v16i& v, float scale) __attribute__((always_inline)) {
+      if (DUMP) {
+        if (k0_of(t) / 32 + j == g.dump_kb) dump_tile(v, a, b);
+      } else {
+        fold(acc[a][b], v, scale);
+      }
+    };
+    // Stage t out of ring slot `slot`; on entry the MFMA of its first tile is in flight in vi[0].  With a next
+    // stage (in slot `nslot`) the MFMA of that stage's first tile is in flight in vi[0] on return.
+    //   keep: stage t + AHEAD exists (its loads may stay in flight over the barrier);
+    //   more: stage t + 1 + AHEAD exists and is prefetched into the slot this stage frees;
+    //   far:  stage t + 3 exists (its scales are requested now).
+    // The flags are compile-time constants everywhere but in the odd first stage.
+    auto run_stage = [&](int t, int slot, int nslot, auto steps_tag, auto has_next, auto keep, auto more, auto far) __attribute__((always_inline)) {
+      constexpr int NT = decltype(steps_tag)::value * NTILE;
+#pragma unroll
+      for (int i = 0; i < NT; ++i) {
+        const int j = i / NTILE, a = (i % NTILE) / WN, b = (i % NTILE) % WN, cur = i & 1;
+        const float scale = sa_c[a][j] * sb_c[b][j];
+        if (i + 1 < NT) {
+          const int j1 = (i + 1) / NTILE, a1 = ((i + 1) % NTILE) / WN, b1 = ((i + 1) % NTILE) % WN;
+          vi[cur ^ 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[j1][b1], fa[j1][a1], zero16, 0, 0, 0);
           __builtin_amdgcn_sched_barrier(0);
-          if (DUMP) {
-            if (s * SPS + j == g.dump_kb) dump_tile(vi[cur], a, b);
-          } else {
-            fold(acc[a][b], vi[cur], sa[a][j] * sb[b][j]);
-          }
+          fold_or_dump(t, j, a, b, vi[cur], scale);
           __builtin_amdgcn_sched_barrier(0);
+        } else if (has_next) {
+          advance_scales(far, SPS);  // before the barrier: the wait there covers the scalar loads
+          wait_loads(keep);
+          if (more) issue_whole(t + 1 + AHEAD, slot);
+          read_frags(nslot);
+          __builtin_amdgcn_sched_barrier(0);
+          fold_or_dump(t, j, a, b, vi[cur], scale);
+          __builtin_amdgcn_sched_barrier(0);
+          vi[0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[0][0], fa[0][0], zero16, 0, 0, 0);
+        } else {
+          fold_or_dump(t, j, a, b, vi[cur], scale);
         }
       }
-    } else {
-      // B = 64 / 128: the INT32 tiles accumulate over KPB K steps inside the MFMA, then are folded.
+    };
+
+    static_assert(NBUF >= 3, "a prefetched stage implies the stage whose scales are requested");
+    advance_scales(true, rem ? rem : SPS);
+    advance_scales(t0 + 1 <= tl, SPS);
+#pragma unroll
+    for (int i = 0; i < AHEAD; ++i)
+      if (t0 + i <= tl) issue(t0 + i, slot_of(t0 + i));
+    wait_loads(t0 + AHEAD - 1 <= tl);
+    if (t0 + AHEAD <= tl) issue(t0 + AHEAD, slot_of(t0 + AHEAD));
+    advance_scales(t0 + 2 <= tl, SPS);
+    read_frags(slot_of(t0));
+    vi[0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[0][0], fa[0][0], zero16, 0, 0, 0);
+    if (rem) {  // the odd first stage: 1 .. SPS-1 K steps, an odd tile count flips the rotation, hence vi[0] again
+      const bool has_next = tl >= 0, keep = AHEAD - 1 <= tl, more = AHEAD <= tl, far = 2 <= tl;
+      if constexpr (SPS >= 2) { if (rem == 1) run_stage(-1, NBUF - 1, 0, std::integral_constant<int, 1>(), has_next, keep, more, far); }
+      if constexpr (SPS >= 4) { if (rem == 2) run_stage(-1, NBUF - 1, 0, std::integral_constant<int, 2>(), has_next, keep, more, far); }
+      if constexpr (SPS >= 4) { if (rem == 3) run_stage(-1, NBUF - 1, 0, std::integral_constant<int, 3>(), has_next, keep, more, far); }
+    }
+    // Main loop: passes of NBUF whole stages, each with a successor and a stage to prefetch, so the ring slot
+    // of every stage is a compile-time constant: LDS addresses are immediates and the accumulators never move.
+    int t = 0;
+    for (; t + 2 * NBUF - 1 <= tl; t += NBUF) {
+      // The instruction arbiter favours the oldest wave of a SIMD, so co-resident waves would finish one after
+      // the other and leave the SIMD to a single wave at the end.  Each wave therefore lowers its own priority
+      // as it advances: whoever is ahead yields, and the waves of a SIMD reach the end together.
+      if (4 * t < nstages) __builtin_amdgcn_s_setprio(3);
+      else if (2 * t < nstages) __builtin_amdgcn_s_setprio(2);
+      else if (4 * t < 3 * nstages) __builtin_amdgcn_s_setprio(1);
+      else __builtin_amdgcn_s_setprio(0);
+#pragma unroll
+      for (int u = 0; u < NBUF; ++u)
+        run_stage(t + u, u, (u + 1) % NBUF, whole_tag, std::true_type(), std::true_type(), std::true_type(), std::true_type());
+    }
+    // The last R = 1 .. 2*NBUF-1 stages as straight-line code per R, so that their flags are constants too.
+    __builtin_amdgcn_s_setprio(0);
+    auto run_tail = [&](auto r_tag) __attribute__((always_inline)) {
+      constexpr int R = decltype(r_tag)::value;
+      static_for<0, R>([&](auto i_tag) __attribute__((always_inline)) {
+        constexpr int i = decltype(i_tag)::value;
+        run_stage(t + i, i % NBUF, (i + 1) % NBUF, whole_tag, std::integral_constant<bool, (i + 1 < R)>(),
+                  std::integral_constant<bool, (i + AHEAD < R)>(), std::integral_constant<bool, (i + 1 + AHEAD < R)>(),
+                  std::integral_constant<bool, (i + 3 < R)>());
+      });
+    };
+    const int R = tl - t + 1;
+    static_for<1, 2 * NBUF>([&](auto r_tag) __attribute__((always_inline)) {
+      if (R == decltype(r_tag)::value) run_tail(r_tag);
+    });
+  } else {
+    // ---- B = 64 / 128: the INT32 tiles accumulate over KPB K steps inside the MFMA, then are folded.
+    // One stage (STEPS K steps) out of buffer `buf`.
+    auto compute = [&](int s, int buf, auto steps_tag) __attribute__((always_inline)) {
+      constexpr int STEPS = decltype(steps_tag)::value;
+      const int8_t* ta = tile_buf(buf);
+      const int8_t* tb = ta + A_BYTES;
+      // this stage's scales were fetched during the previous stage; fetch the next stage's now
+      rotate_scales();
+      if (s + 1 < nstages) load_scales(s + 1);
+      float (&sa)[WM][SPS] = sa_c;
+      float (&sb)[WN][SPS] = sb_c;
 #pragma unroll
       for (int j = 0; j < STEPS; ++j) {
         v4i fa[WM], fb[WN];
@@ -348,65 +508,33 @@ __global__ void __launch_bounds__(64 * WGM * WGN, WMIN) gemm_kernel(const GemmAr
           }
         }
       }
-    }
-  };
-
-  // Stage loop over the ring of NBUF LDS buffers: while stage s is computed, stages s+1 .. s+NBUF-1
-  // are in flight, which covers the L2 latency even when a stage is only two K steps long.  The loop
-  // is unrolled NBUF times so that every LDS address is a compile-time immediate and the accumulators
-  // stay in the same registers; the last (at most NBUF) stages run from a generic copy after the loop.
-  constexpr int LOADS = CA + CB;  // vector-memory instructions per wave and stage
-  constexpr int AHEAD = NBUF - 1;                   // stages issued ahead of the one being computed
-  static_assert(LOADS * (AHEAD - 1) <= 63, "vmcnt immediate");
-  // End of a stage: wait for this wave's own loads of the stage that is read next, then meet the other waves.
-  // A bare s_barrier is used instead of __syncthreads(): the fence of the latter makes the compiler drain
-  // every outstanding load (vmcnt(0)), including the stage that is meant to stay in flight.  Ordering is kept
-  // by hand: the asm is a compiler barrier for memory accesses, each wave has consumed all its LDS reads of the
-  // finished stage before it arrives, and direct-to-LDS loads are counted by vmcnt.
-  auto wait_loads = [&](bool keep_in_flight) {  // true: the AHEAD-1 youngest stages may stay outstanding
-    if (!keep_in_flight || AHEAD == 1) asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
-    else asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(LOADS * (AHEAD - 1)) : "memory");
-  };
-  const std::integral_constant<int, SPS> whole_tag;
-  // the last stage of a K that is not a multiple of KC holds 1 .. SPS-1 K steps (whole quantization blocks)
-  auto compute_partial = [&](int s, int buf) {
-    const int rem = nsteps - s * SPS;
-    if constexpr (SPS >= 2 && KPB <= 1) { if (rem == 1) compute(s, buf, std::integral_constant<int, 1>()); }
-    if constexpr (SPS >= 4 && KPB <= 2) { if (rem == 2) compute(s, buf, std::integral_constant<int, 2>()); }
-    if constexpr (SPS >= 4 && KPB <= 1) { if (rem == 3) compute(s, buf, std::integral_constant<int, 3>()); }
-  };
-  const int nwhole = g.K / KC;
-  load_scales(0);
+    };
+    auto compute_partial = [&](int s, int buf) __attribute__((always_inline)) {
+      const int rem = nsteps - s * SPS;
+      if constexpr (SPS >= 4 && KPB <= 2) { if (rem == 2) compute(s, buf, std::integral_constant<int, 2>()); }
+    };
+    load_scales(0);
 #pragma unroll
-  for (int i = 0; i < AHEAD; ++i)
-    if (i < nstages) issue(i, i);
-  wait_loads(nstages >= AHEAD);
-  int s = 0;
-  // inside this loop stage s + NBUF + AHEAD - 1 .. exist for every issue, and every computed stage is whole
-  for (; s + NBUF <= nwhole && s + NBUF + AHEAD - 1 < nstages; s += NBUF) {
-    // The instruction arbiter favours the oldest wave of a SIMD, so co-resident waves would finish one after
-    // the other and leave the SIMD to a single wave at the end.  Each wave therefore lowers its own priority
-    // as it advances: whoever is ahead yields, and the waves of a SIMD reach the end together.
-    {
-      const int quarter = (4 * s) / nstages;
-      if (quarter == 0) __builtin_amdgcn_s_setprio(3);
-      else if (quarter == 1) __builtin_amdgcn_s_setprio(2);
-      else if (quarter == 2) __builtin_amdgcn_s_setprio(1);
-      else __builtin_amdgcn_s_setprio(0);
-    }
+    for (int i = 0; i < AHEAD; ++i)
+      if (i < nstages) issue_at(i * KC, i, false);
+    wait_loads(nstages >= AHEAD);
+    int s = 0;
+    // inside this loop stage s + NBUF + AHEAD - 1 .. exist for every issue, and every computed stage is whole
+    for (; s + NBUF <= nwhole && s + NBUF + AHEAD - 1 < nstages; s += NBUF) {
 #pragma unroll
-    for (int u = 0; u < NBUF; ++u) {
-      issue(s + u + AHEAD, (u + AHEAD) % NBUF);
-      compute(s + u, u, whole_tag);
-      wait_loads(true);
+      for (int u = 0; u < NBUF; ++u) {
+        issue_at((s + u + AHEAD) * KC, (u + AHEAD) % NBUF, false);
+        compute(s + u, u, whole_tag);
+        wait_loads(true);
+      }
     }
-  }
-  for (int buf = s % NBUF; s < nstages; ++s, buf = (buf + 1 == NBUF ? 0 : buf + 1)) {
-    const bool more = s + AHEAD < nstages;
-    if (more) issue(s + AHEAD, (buf + AHEAD) % NBUF);
-    if (s < nwhole) compute(s, buf, whole_tag);
-    else compute_partial(s, buf);
-    wait_loads(more);
+    for (int buf = s % NBUF; s < nstages; ++s, buf = (buf + 1 == NBUF ? 0 : buf + 1)) {
+      const bool more = s + AHEAD < nstages;
+      if (more) issue_at((s + AHEAD) * KC, (buf + AHEAD) % NBUF, false);
+      if (s < nwhole) compute(s, buf, whole_tag);
+      else compute_partial(s, buf);
+      wait_loads(more);
+    }
   }
   if (DUMP) return;
 

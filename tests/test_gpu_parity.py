@@ -146,6 +146,39 @@ def test_linear_every_tile_shape(shape, block, N, C, D):
         jf.jf_debug_set_gemm_shape(0)
 
 
+_K_SWEEP_CACHE = {}
+
+
+def _k_sweep_case(nsteps):
+    """Oracle results of a layer whose three contraction lengths are all 32 * nsteps (computed once per length)."""
+    if nsteps not in _K_SWEEP_CACHE:
+        n = 32 * nsteps
+        (X, SX), (W, SW), (dY, SdY) = _quantized_layer(3900 + nsteps, n, n, n, 32)
+        _K_SWEEP_CACHE[nsteps] = ((X, SX, W, SW, dY, SdY),
+                                  oracle.linear_fwd(X, SX, W, SW, 32)[2], oracle.linear_dgrad(dY, SdY, W, SW, 32)[2],
+                                  oracle.linear_wgrad(dY, SdY, X, SX, 32)[2])
+    return _K_SWEEP_CACHE[nsteps]
+
+
+@pytest.mark.parametrize("shape", [1, 2, 3, 4])
+def test_linear_k_loop_every_stage_count(shape):
+    """The K loop of the block-32 kernels is a software pipeline whose prologue, main passes and last stages are
+    separate code for every count of remaining stages, with the odd K steps of a stage-unaligned K run first.
+    Sweep the number of 32-wide K steps so that every one of those paths runs, for every tile shape and for all
+    three operand layouts; the FP32 accumulators must match the oracle's FP32 accumulators bit for bit."""
+    jf.jf_debug_set_gemm_shape(shape)
+    try:
+        for nsteps in list(range(1, 19)) + [23, 24, 31, 32, 33, 35, 36, 41, 47]:
+            say(f"tile shape {shape}: {nsteps} K steps")
+            (X, SX, W, SW, dY, SdY), f_fwd, f_dgrad, f_wgrad = _k_sweep_case(nsteps)
+            Xd, SXd, Wd, SWd, dYd, SdYd = map(dev, (X, SX, W, SW, dY, SdY))
+            np.testing.assert_array_equal(host(jf.jf_linear_fwd(Xd, SXd, Wd, SWd, 32, want_f32=True)[2]), f_fwd)
+            np.testing.assert_array_equal(host(jf.jf_linear_dgrad(dYd, SdYd, Wd, SWd, 32, want_f32=True)[2]), f_dgrad)
+            np.testing.assert_array_equal(host(jf.jf_linear_wgrad(dYd, SdYd, Xd, SXd, 32, want_f32=True)[2]), f_wgrad)
+    finally:
+        jf.jf_debug_set_gemm_shape(0)
+
+
 def test_linear_zero_blocks_and_run_to_run_stability():
     block, N, C, D = 32, 128, 128, 128
     (X, SX), (W, SW), _ = _quantized_layer(3100, N, C, D, block)

@@ -39,6 +39,8 @@ def parse_args():
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="oracle time budget of the CPU baseline leg")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also launch plain 256 MiB device copies, the reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE")
+    ap.add_argument("--event-every", type=int, default=8,
+                    help="bracket the GEMM launches with HIP events on every n-th timed step only")
     ap.add_argument("--graph", action="store_true", help="also time the step replayed from a captured HIP graph")
     return ap.parse_args()
 
@@ -151,8 +153,8 @@ def main():
         step(False)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step(True)
+    for i in range(args.steps):
+        step(i % args.event_every == 0)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = dt / args.steps * 1e3
@@ -186,7 +188,7 @@ def main():
 
     gemm_ms = [e0.elapsed_time(e1) for e0, e1 in gemm_events]
     gemm_avg_ms = sum(gemm_ms) / len(gemm_ms)
-    per_gemm = [sum(gemm_ms[i::3]) / args.steps for i in range(3)]
+    per_gemm = [sum(gemm_ms[i::3]) / len(gemm_ms[i::3]) for i in range(3)]
     gemm_ops = 2.0 * N * C * D
     achieved = gemm_ops / (gemm_avg_ms * 1e-3) * 1e-12
 

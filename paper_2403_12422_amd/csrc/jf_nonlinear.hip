@@ -50,18 +50,9 @@ __device__ __forceinline__ TailEval normal_tail(float a) {
   return r;
 }
 
-// GELU(x) = x Phi(x) = max(x, 0) - |x| Q(|x|)     (App. A)
-__device__ __forceinline__ float gelu_value(float x) {
-  const float a = fabsf(x);
-  return fmaxf(x, 0.0f) - a * normal_tail(a).q;
-}
-// dGELU/dx = x phi(x) + Phi(x),  phi(x) = exp(-x^2/2) / sqrt(2 pi),  Phi(x) = x > 0 ? 1 - Q : Q     (App. A)
-__device__ __forceinline__ float gelu_slope(float x) {
-  const float a = fabsf(x);
-  const TailEval te = normal_tail(a);
-  const float cdf = x > 0.0f ? 1.0f - te.q : te.q;
-  return __builtin_fmaf(x * 0.39894228040143268f, te.ez, cdf);
-}
+// Both table functions are written in terms of the upper tail Q(|x|) of the normal distribution (App. A):
+//   GELU(x) = x Phi(x) = max(x, 0) - |x| Q(|x|),
+//   dGELU/dx = x phi(x) + Phi(x),  phi(x) = exp(-x^2/2) / sqrt(2 pi),  Phi(x) = x > 0 ? 1 - Q(|x|) : Q(|x|).
 
 // ------------------------------------------------------------------------------------------------
 __device__ __forceinline__ float amax4(float m, float a, float b, float c, float d) {
@@ -117,14 +108,30 @@ __global__ void __launch_bounds__(256) gelu_kernel(const int8_t* __restrict__ X,
   const bool col_ok = col < cols;  // cols % 32 == 0 and chunks are 16 wide: a 32-column group is all in or all out
   const int lc = cols / B, bi = blockIdx.y;
 
-  // tabulate f(code * scale) for the 256 byte values of each block of this workgroup
+  // Tabulate f(code * scale) for the byte values of each block of this workgroup.  Both functions are
+  // built from the upper tail Q(|x|), so one tail evaluation serves the codes +i and -i: 128 evaluations
+  // per table.  Entry 128 (code -128, which no quantizer output holds) is set to 0.
+  {
+    const int i = threadIdx.x & 127;
 #pragma unroll
-  for (int k = 0; k < NTAB; ++k) {
-    const int bcol = c0 + k * B;
-    if (bcol < cols) {
-      const float s = SX[(int64_t)bi * lc + bcol / B];
-      const float x = (float)(int8_t)threadIdx.x * s;
-      s_tab[k][threadIdx.x] = BWD ? gelu_slope(x) : gelu_value(x);
+    for (int k = threadIdx.x >> 7; k < NTAB; k += 2) {
+      const int bcol = c0 + k * B;
+      if (bcol < cols) {
+        const float a = (float)i * SX[(int64_t)bi * lc + bcol / B];
+        const TailEval te = normal_tail(a);
+        float pos, neg;  // f(+a), f(-a)
+        if (BWD) {       // x phi(x) + Phi(x)
+          const float slope = a * 0.39894228040143268f;
+          pos = __builtin_fmaf(slope, te.ez, 1.0f - te.q);
+          neg = __builtin_fmaf(-slope, te.ez, te.q);
+        } else {         // max(x, 0) - |x| Q(|x|)
+          const float aq = a * te.q;
+          pos = a - aq;
+          neg = 0.0f - aq;
+        }
+        s_tab[k][i] = pos;
+        s_tab[k][i == 0 ? 128 : 256 - i] = i == 0 ? 0.0f : neg;
+      }
     }
   }
   __syncthreads();

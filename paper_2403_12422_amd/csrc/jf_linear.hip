@@ -46,8 +46,9 @@ struct GemmArgs {
 // ds_write; the 64 lanes of one such instruction fill 64 consecutive 16-byte LDS slots, so the
 // layout cannot be padded.  Bank conflicts are avoided by an XOR swizzle instead: the tile is a
 // matrix of 16-byte chunks with CPR chunks per row, and chunk c of row r lives in slot
-// r*CPR + (c ^ swz(r)); swz makes 8 consecutive rows at a fixed c cover all 8 bank groups, which
-// is what both ds_read_b128 (K-major operand) and ds_read_b64_tr_b8 (M-major operand) need.
+// r*CPR + (c ^ swz(r)); swz is chosen per operand layout so that the lanes one fragment read serves per
+// clock (16 rows for ds_read_b128 of a K-major operand, 8 rows for ds_read_b64_tr_b8 of an M-major one)
+// fall into different bank groups.
 template <int TILE, bool KMAJOR, int KC>
 struct TileLayout {
   static constexpr int kRows = KMAJOR ? TILE : KC;            // LDS rows: output rows, or K rows
@@ -56,7 +57,16 @@ struct TileLayout {
   static_assert(kCPR == 4 || kCPR == 6 || kCPR == 8, "rows of 64, 96 or 128 bytes");
   // 96-byte rows (a 96-wide M-major tile) are left unswizzled: their fragment reads see two-way bank
   // conflicts, which the vector-ALU-bound B = 32 loop does not notice.
-  static __device__ __forceinline__ int swz(int r) { return kCPR == 6 ? 0 : (r / (kCPR == 4 ? 2 : 1)) % kCPR; }
+  // K-major tiles are read with ds_read_b128, which serves 16 lanes (16 consecutive rows, one chunk each) per
+  // clock from 256 bytes of banks: the 16 rows must land in 16 different 16-byte bank groups.  A row of 128
+  // (64) bytes starts at bank group 8*(r%2) (4*(r%4)), so the XOR term has to run through its 8 (4) values
+  // over the rows that share that start.  M-major tiles are read with 8-byte transposing reads, 8 rows per
+  // 16 lanes: 8 consecutive rows at a fixed chunk cover 8 bank groups.
+  static __device__ __forceinline__ int swz(int r) {
+    if (kCPR == 6) return 0;
+    if (KMAJOR) return (r / (16 / kCPR)) % kCPR;
+    return (r / (kCPR == 4 ? 2 : 1)) % kCPR;
+  }
   static __device__ __forceinline__ int slot(int r, int c) { return r * kCPR + (c ^ swz(r)); }
   // LDS bytes when the tile is filled by whole 64-lane load instructions of NW waves (the tail is padding)
   static constexpr int bytes(int nw) { return ((kSlots + 64 * nw - 1) / (64 * nw)) * (64 * nw) * 16; }
@@ -135,9 +145,10 @@ __device__ __forceinline__ void static_for(F&& f) {
 // acc += t * (float)v for one 32x32 sub-block (Sec. 5.3): 16 int->float conversions and 16 FMAs per lane.
 // The fused multiply-add is written as v_fmac_f32 so that it updates the accumulator register in place;
 // left to itself the register allocator ping-pongs the 64 accumulators between two register sets.
+template <int R0 = 0, int R1 = 16>
 __device__ __forceinline__ void fold(float (&acc)[16], const v16i& v, float t) {
 #pragma unroll
-  for (int r = 0; r < 16; ++r) {
+  for (int r = R0; r < R1; ++r) {
     const float c = (float)v[r];
     asm("v_fmac_f32 %0, %1, %2" : "+v"(acc[r]) : "v"(t), "v"(c));
   }
@@ -149,10 +160,11 @@ __global__ void __launch_bounds__(64 * WGM * WGN, WMIN) gemm_kernel(const GemmAr
   constexpr int NW = WGM * WGN;
   constexpr int TM = 32 * WM * WGM, TN = 32 * WN * WGN;
   constexpr int KPB = B / 32;  // MFMA K steps per quantization block
-  // K bytes per stage: 128 when a stage has to hold a whole B = 128 block, or for the workgroups of nine or
-  // twelve waves (one per compute unit), whose barriers are the most expensive; 64 otherwise, which lets three
+  // K bytes per stage: 128 when a stage has to hold a whole B = 128 block, for the workgroups of more than
+  // four waves (one per compute unit), whose barriers are the most expensive, and for the one-sub-block waves at
+  // B = 64 (a stage must hold an even number of sub-block x K-block units); 64 otherwise, which lets three
   // workgroups with a ring of three stages share the LDS of a compute unit.
-  constexpr int KC = (B == 128 || WGM * WGN > 4) ? 128 : 64;
+  constexpr int KC = (B == 128 || WGM * WGN > 4 || (B == 64 && WM * WN == 1)) ? 128 : 64;
   constexpr int SPS = KC / 32;  // MFMA K steps per stage
   constexpr int NTILE = WM * WN;
   typedef TileLayout<TM, AK, KC> LA;
@@ -162,10 +174,10 @@ __global__ void __launch_bounds__(64 * WGM * WGN, WMIN) gemm_kernel(const GemmAr
   static_assert(B == 32 || (TM % B == 0 && TN % B == 0), "tile must hold whole quantization blocks");
   constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
 
-  // Stages in the LDS ring: one being read, the rest in flight.  Three stages of a 128x128 tile with KC = 128
-  // would not fit the 160 KB of LDS, so B = 128 runs a ring of two.
-  // Tiles that leave a compute unit to a single workgroup (more than four waves) take a ring of four.
-  constexpr int NBUF = (KC == 128 && STAGE_BYTES > 40 * 1024) ? 2 : (NW > 4 ? 4 : 3);
+  // Stages in the LDS ring: one being read, the rest in flight.  Tiles that leave a compute unit to a single
+  // workgroup (more than four waves) take a ring of four, the others a ring of three.
+  constexpr int NBUF = NW > 4 ? 4 : 3;
+  static_assert(NBUF * STAGE_BYTES <= 160 * 1024, "the ring must fit the LDS of a compute unit");
   // One LDS variable per ring slot: the compiler tracks direct-to-LDS loads per variable, so a read of
   // one slot does not make it wait for the loads still flying into the other slots.
   __shared__ __align__(1024) int8_t s_tile0[STAGE_BYTES];
@@ -181,12 +193,17 @@ __global__ void __launch_bounds__(64 * WGM * WGN, WMIN) gemm_kernel(const GemmAr
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm0 = (wave / WGN) * WM, wn0 = (wave % WGN) * WN;  // first 32-granule of this wave inside the tile
 
-  // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  Renumber them so that
-  // every XCD works on one contiguous band of tiles and re-reads its operands from its own L2.
-  const int ntiles = gridDim.x, tiles_n = (g.Nn + TN - 1) / TN;
+  // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  Renumber them so that every XCD
+  // works on one contiguous run of tiles, and order the tiles in groups of GROUP_M tile rows, column by column
+  // inside a group: the workgroups that are resident on an XCD at the same time then form a compact patch
+  // (8 tile rows x a few tile columns) that re-reads few distinct operand tiles from that XCD's L2.
+  constexpr int GROUP_M = 8;
+  const int ntiles = gridDim.x, tiles_n = (g.Nn + TN - 1) / TN, tiles_m = (g.M + TM - 1) / TM;
   const int xcd = blockIdx.x & 7, idx = blockIdx.x >> 3;
   const int tile = xcd * (ntiles >> 3) + min(xcd, ntiles & 7) + idx;
-  const int m0 = (tile / tiles_n) * TM, n0 = (tile % tiles_n) * TN;
+  const int group = tile / (GROUP_M * tiles_n), first_m = group * GROUP_M;
+  const int in_group = tile - group * GROUP_M * tiles_n, group_rows = min(GROUP_M, tiles_m - first_m);
+  const int m0 = (first_m + in_group % group_rows) * TM, n0 = (in_group / group_rows) * TN;
 
   const int nsteps = g.K / 32;
   const int nstages = (g.K + KC - 1) / KC;
@@ -199,10 +216,10 @@ __global__ void __launch_bounds__(64 * WGM * WGN, WMIN) gemm_kernel(const GemmAr
 #pragma unroll
   for (int i = 0; i < CB; ++i) srcB[i] = g.Bm + chunk_offset<TN, BK, KC>((i * NW + wave) * 64 + lane, n0, 0, g.Nn, g.K, g.ldb);
   const int64_t kstrideA = AK ? 1 : g.lda, kstrideB = BK ? 1 : g.ldb;
-  // Block scales are wave-uniform: they are read with scalar loads straight into SGPRs, one stage ahead
-  // (sa_n / sb_n), so they cost neither LDS traffic nor vector-memory slots.  Index [a][j]: sub-tile a of the
-  // wave, K step j of the stage.  Granules or K steps outside the matrix are clamped (their products are unused).
-  float sa_c[WM][SPS], sb_c[WN][SPS], sa_n[WM][SPS], sb_n[WN][SPS];
+  // Block scales are wave-uniform: they are read with scalar loads straight into SGPRs, ahead of their use,
+  // so they cost neither LDS traffic nor vector-memory slots.  Index [a][j]: sub-tile a of the wave,
+  // quantization block j of the stage along K.  Granules outside the matrix are clamped (their products are unused).
+  float sa_c[WM][SPS / KPB], sb_c[WN][SPS / KPB], sa_n[WM][SPS / KPB], sb_n[WN][SPS / KPB];
   int sa_row[WM], sb_row[WN];
 #pragma unroll
   for (int a = 0; a < WM; ++a) sa_row[a] = (min(m0 + 32 * (wm0 + a), g.M - 32) / B) * g.sa_p;
@@ -212,20 +229,9 @@ __global__ void __launch_bounds__(64 * WGM * WGN, WMIN) gemm_kernel(const GemmAr
   // uniform load from that space is selected as a scalar load.
   typedef const __attribute__((address_space(4))) float* const_f32_ptr;
   const const_f32_ptr SAc = (const_f32_ptr)g.SA, SBc = (const_f32_ptr)g.SB;
-  auto load_scales = [&](int s) __attribute__((always_inline)) {
-    if (DUMP) return;
-#pragma unroll
-    for (int j = 0; j < SPS; ++j) {
-      const int kb = min(s * KC + 32 * j, g.K - 32) / B;
-#pragma unroll
-      for (int a = 0; a < WM; ++a) sa_n[a][j] = SAc[sa_row[a] + (int64_t)kb * g.sa_k];
-#pragma unroll
-      for (int b = 0; b < WN; ++b) sb_n[b][j] = SBc[sb_row[b] + (int64_t)kb * g.sb_k];
-    }
-  };
   auto rotate_scales = [&]() __attribute__((always_inline)) {
 #pragma unroll
-    for (int j = 0; j < SPS; ++j) {
+    for (int j = 0; j < SPS / KPB; ++j) {
 #pragma unroll
       for (int a = 0; a < WM; ++a) sa_c[a][j] = sa_n[a][j];
 #pragma unroll
@@ -272,7 +278,6 @@ __global__ void __launch_bounds__(64 * WGM * WGN, WMIN) gemm_kernel(const GemmAr
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.0f;
   const v16i zero16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-  v16i vchain[KPB > 1 ? NTILE : 1];  // INT32 tiles carried across K steps (B > 32 only)
 
   auto dump_tile = [&](const v16i& v, int a, int b) __attribute__((always_inline)) {
     const int m = m0 + 32 * (wm0 + a) + (lane & 31);
@@ -312,230 +317,186 @@ __global__ void __launch_bounds__(64 * WGM * WGN, WMIN) gemm_kernel(const GemmAr
   const std::integral_constant<int, SPS> whole_tag;
   const int nwhole = g.K / KC;
 
-  if constexpr (KPB == 1) {
-    // ---- B = 32: every MFMA result is folded right away, and the kernel is bound by those conversions and
-    // FMAs.  The wave keeps one software pipeline running across the stage barriers: two INT32 tiles rotate,
-    // the MFMA of the next tile is issued before the 32 conversions/FMAs of the current one, and at the end
-    // of a stage the barrier, the prefetch and the fragment reads of the next stage come BEFORE the fold of
-    // the stage's last tile, which covers the LDS latency of those reads.  All fragments of a stage are read
-    // at once (they fit the registers of the double buffer they replace).
-    static_assert((SPS * NTILE) % 2 == 0, "a whole stage leaves the tile rotation where it found it");
-    v16i vi[2];
-    v4i fa[SPS][WM], fb[SPS][WN];
-    // scales two stages ahead of the one in use: requested before a stage barrier, moved one level down at
-    // the next, so the scalar loads are never waited for together with LDS fragment reads
-    float sa_f[WM][SPS], sb_f[WN][SPS];
+  // ---- One software pipeline per wave that runs across the stage barriers.  The unit is the product of one
+  // 32x32 sub-block with one quantization block along K: a chain of KPB MFMAs into one INT32 tile, then the
+  // fold of that tile into the FP32 accumulator (32 conversions/FMAs; at B = 32 the kernel is bound by them).
+  // Two INT32 tiles rotate: the chain of the next unit is issued before the fold of the current one, and at
+  // the end of a stage the barrier, the prefetch and the fragment reads of the next stage come BEFORE the fold
+  // of the stage's last unit, which covers the LDS latency of those reads.  All fragments of a stage are read
+  // at once.
+  constexpr int NKB = SPS / KPB;  // quantization blocks along K per stage
+  static_assert(SPS % KPB == 0 && (NKB * NTILE) % 2 == 0, "a whole stage leaves the tile rotation where it found it");
+  v16i vi[2];
+  v4i fa[SPS][WM], fb[SPS][WN];
+  // scales two stages ahead of the one in use: requested before a stage barrier, moved one level down at
+  // the next, so the scalar loads are never waited for together with LDS fragment reads
+  float sa_f[WM][NKB], sb_f[WN][NKB];
+#pragma unroll
+  for (int j = 0; j < NKB; ++j) {
+#pragma unroll
+    for (int a = 0; a < WM; ++a) sa_c[a][j] = sa_n[a][j] = sa_f[a][j] = 0.0f;
+#pragma unroll
+    for (int b = 0; b < WN; ++b) sb_c[b][j] = sb_n[b][j] = sb_f[b][j] = 0.0f;
+  }
+  // Stages are numbered t = t0 .. tl.  When K is not a multiple of KC the odd K steps (whole quantization
+  // blocks) come FIRST, as stage t = -1 in ring slot NBUF-1, so that every stage inside the loops is whole;
+  // stage t >= 0 starts at K offset kbase + t*KC and lives in ring slot t % NBUF.
+  const int rem = nsteps % SPS, kbase = 32 * rem;
+  const int t0 = rem ? -1 : 0, tl = nwhole - 1;
+  // Running scalar pointers to the scales of the next stage to request: one 64-bit add per stage and
+  // operand sub-tile instead of an index computation per load.
+  const_f32_ptr pa[WM], pb[WN];
+#pragma unroll
+  for (int a = 0; a < WM; ++a) pa[a] = SAc + sa_row[a];
+#pragma unroll
+  for (int b = 0; b < WN; ++b) pb[b] = SBc + sb_row[b];
+  // current <- next <- far <- scalar loads of `blocks` quantization blocks along K (the rest of a stage keeps
+  // stale values that are never used); nothing is requested when the far stage does not exist
+  auto advance_scales = [&](auto far_exists, int blocks) __attribute__((always_inline)) {
+    rotate_scales();
+#pragma unroll
+    for (int j = 0; j < NKB; ++j) {
+#pragma unroll
+      for (int a = 0; a < WM; ++a) sa_n[a][j] = sa_f[a][j];
+#pragma unroll
+      for (int b = 0; b < WN; ++b) sb_n[b][j] = sb_f[b][j];
+    }
+    if (DUMP) return;
+    if (far_exists) {
+#pragma unroll
+      for (int j = 0; j < NKB; ++j) {
+        if (j < blocks) {
+#pragma unroll
+          for (int a = 0; a < WM; ++a) sa_f[a][j] = pa[a][j * g.sa_k];
+#pragma unroll
+          for (int b = 0; b < WN; ++b) sb_f[b][j] = pb[b][j * g.sb_k];
+        }
+      }
+#pragma unroll
+      for (int a = 0; a < WM; ++a) pa[a] += blocks * g.sa_k;
+#pragma unroll
+      for (int b = 0; b < WN; ++b) pb[b] += blocks * g.sb_k;
+    }
+  };
+  // stages t >= 0 are whole by construction
+  auto issue = [&](int t, int slot) __attribute__((always_inline)) { issue_at(max(0, 32 * (nsteps % SPS) + t * KC), slot, false); };
+  auto issue_whole = [&](int t, int slot) __attribute__((always_inline)) { issue_at(32 * (nsteps % SPS) + t * KC, slot, std::true_type()); };
+  auto read_frags = [&](int buf) __attribute__((always_inline)) {
+    const int8_t* ta = tile_buf(buf);
+    const int8_t* tb = ta + A_BYTES;
 #pragma unroll
     for (int j = 0; j < SPS; ++j) {
 #pragma unroll
-      for (int a = 0; a < WM; ++a) sa_c[a][j] = sa_n[a][j] = sa_f[a][j] = 0.0f;
+      for (int a = 0; a < WM; ++a) fa[j][a] = addrA.read(ta, a, j);
 #pragma unroll
-      for (int b = 0; b < WN; ++b) sb_c[b][j] = sb_n[b][j] = sb_f[b][j] = 0.0f;
+      for (int b = 0; b < WN; ++b) fb[j][b] = addrB.read(tb, b, j);
     }
-    // Stages are numbered t = t0 .. tl.  When K is not a multiple of KC the odd K steps come FIRST, as stage
-    // t = -1 in ring slot NBUF-1, so that every stage inside the loops is whole; stage t >= 0 starts at K
-    // offset kbase + t*KC and lives in ring slot t % NBUF.
-    const int rem = nsteps % SPS, kbase = 32 * rem;
-    const int t0 = rem ? -1 : 0, tl = nwhole - 1;
-    // Running scalar pointers to the scales of the next stage to request: one 64-bit add per stage and
-    // operand sub-tile instead of an index computation per load.
-    const_f32_ptr pa[WM], pb[WN];
-#pragma unroll
-    for (int a = 0; a < WM; ++a) pa[a] = SAc + sa_row[a];
-#pragma unroll
-    for (int b = 0; b < WN; ++b) pb[b] = SBc + sb_row[b];
-    // current <- next <- far <- scalar loads of `steps` K steps (the rest of a stage keeps stale values that
-    // are never used); nothing is requested when the far stage does not exist
-    auto advance_scales = [&](auto far_exists, int steps) __attribute__((always_inline)) {
-      rotate_scales();
-#pragma unroll
-      for (int j = 0; j < SPS; ++j) {
-#pragma unroll
-        for (int a = 0; a < WM; ++a) sa_n[a][j] = sa_f[a][j];
-#pragma unroll
-        for (int b = 0; b < WN; ++b) sb_n[b][j] = sb_f[b][j];
-      }
-      if (DUMP) return;
-      if (far_exists) {
-#pragma unroll
-        for (int j = 0; j < SPS; ++j) {
-          if (j < steps) {
-#pragma unroll
-            for (int a = 0; a < WM; ++a) sa_f[a][j] = pa[a][j * g.sa_k];
-#pragma unroll
-            for (int b = 0; b < WN; ++b) sb_f[b][j] = pb[b][j * g.sb_k];
-          }
-        }
-#pragma unroll
-        for (int a = 0; a < WM; ++a) pa[a] += steps * g.sa_k;
-#pragma unroll
-        for (int b = 0; b < WN; ++b) pb[b] += steps * g.sb_k;
-      }
-    };
-    // stages t >= 0 are whole by construction
-    auto issue = [&](int t, int slot) __attribute__((always_inline)) { issue_at(max(0, 32 * (nsteps % SPS) + t * KC), slot, false); };
-    auto issue_whole = [&](int t, int slot) __attribute__((always_inline)) { issue_at(32 * (nsteps % SPS) + t * KC, slot, std::true_type()); };
-    auto read_frags = [&](int buf) __attribute__((always_inline)) {
-      const int8_t* ta = tile_buf(buf);
-      const int8_t* tb = ta + A_BYTES;
-#pragma unroll
-      for (int j = 0; j < SPS; ++j) {
-#pragma unroll
-        for (int a = 0; a < WM; ++a) fa[j][a] = addrA.read(ta, a, j);
-#pragma unroll
-        for (int b = 0; b < WN; ++b) fb[j][b] = addrB.read(tb, b, j);
-      }
-    };
-    auto k0_of = [&](int t) __attribute__((always_inline)) { return max(0, kbase + t * KC); };
-    auto slot_of = [&](int t) __attribute__((always_inline)) { return (t + NBUF) % NBUF; };
-    auto fold_or_dump = [&](int t, int j, int a, int b, const v16i& v, float scale) __attribute__((always_inline)) {
-      if (DUMP) {
-        if (k0_of(t) / 32 + j == g.dump_kb) dump_tile(v, a, b);
-      } else {
-        fold(acc[a][b], v, scale);
-      }
-    };
-    // Stage t out of ring slot `slot`; on entry the MFMA of its first tile is in flight in vi[0].  With a next
-    // stage (in slot `nslot`) the MFMA of that stage's first tile is in flight in vi[0] on return.
-    //   keep: stage t + AHEAD exists (its loads may stay in flight over the barrier);
-    //   more: stage t + 1 + AHEAD exists and is prefetched into the slot this stage frees;
-    //   far:  stage t + 3 exists (its scales are requested now).
-    // The flags are compile-time constants everywhere but in the odd first stage.
-    auto run_stage = [&](int t, int slot, int nslot, auto steps_tag, auto has_next, auto keep, auto more, auto far) __attribute__((always_inline)) {
-      constexpr int NT = decltype(steps_tag)::value * NTILE;
-#pragma unroll
-      for (int i = 0; i < NT; ++i) {
-        const int j = i / NTILE, a = (i % NTILE) / WN, b = (i % NTILE) % WN, cur = i & 1;
-        const float scale = sa_c[a][j] * sb_c[b][j];
-        if (i + 1 < NT) {
-          const int j1 = (i + 1) / NTILE, a1 = ((i + 1) % NTILE) / WN, b1 = ((i + 1) % NTILE) % WN;
-          vi[cur ^ 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[j1][b1], fa[j1][a1], zero16, 0, 0, 0);
-          __builtin_amdgcn_sched_barrier(0);
-          fold_or_dump(t, j, a, b, vi[cur], scale);
-          __builtin_amdgcn_sched_barrier(0);
-        } else if (has_next) {
-          advance_scales(far, SPS);  // before the barrier: the wait there covers the scalar loads
-          wait_loads(keep);
-          if (more) issue_whole(t + 1 + AHEAD, slot);
-          read_frags(nslot);
-          __builtin_amdgcn_sched_barrier(0);
-          fold_or_dump(t, j, a, b, vi[cur], scale);
-          __builtin_amdgcn_sched_barrier(0);
-          vi[0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[0][0], fa[0][0], zero16, 0, 0, 0);
-        } else {
-          fold_or_dump(t, j, a, b, vi[cur], scale);
-        }
-      }
-    };
-
-    static_assert(NBUF >= 3, "a prefetched stage implies the stage whose scales are requested");
-    advance_scales(true, rem ? rem : SPS);
-    advance_scales(t0 + 1 <= tl, SPS);
-#pragma unroll
-    for (int i = 0; i < AHEAD; ++i)
-      if (t0 + i <= tl) issue(t0 + i, slot_of(t0 + i));
-    wait_loads(t0 + AHEAD - 1 <= tl);
-    if (t0 + AHEAD <= tl) issue(t0 + AHEAD, slot_of(t0 + AHEAD));
-    advance_scales(t0 + 2 <= tl, SPS);
-    read_frags(slot_of(t0));
-    vi[0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[0][0], fa[0][0], zero16, 0, 0, 0);
-    if (rem) {  // the odd first stage: 1 .. SPS-1 K steps, an odd tile count flips the rotation, hence vi[0] again
-      const bool has_next = tl >= 0, keep = AHEAD - 1 <= tl, more = AHEAD <= tl, far = 2 <= tl;
-      if constexpr (SPS >= 2) { if (rem == 1) run_stage(-1, NBUF - 1, 0, std::integral_constant<int, 1>(), has_next, keep, more, far); }
-      if constexpr (SPS >= 4) { if (rem == 2) run_stage(-1, NBUF - 1, 0, std::integral_constant<int, 2>(), has_next, keep, more, far); }
-      if constexpr (SPS >= 4) { if (rem == 3) run_stage(-1, NBUF - 1, 0, std::integral_constant<int, 3>(), has_next, keep, more, far); }
+  };
+  auto k0_of = [&](int t) __attribute__((always_inline)) { return max(0, kbase + t * KC); };
+  auto slot_of = [&](int t) __attribute__((always_inline)) { return (t + NBUF) % NBUF; };
+  // registers [16*part/KPB, 16*(part+1)/KPB) of one unit's fold (the test hook stores the whole tile at part 0)
+  auto fold_or_dump = [&](int t, int kb, int a, int b, const v16i& v, float scale, auto part_tag) __attribute__((always_inline)) {
+    constexpr int part = decltype(part_tag)::value;
+    if (DUMP) {
+      if (part == 0 && k0_of(t) / B + kb == g.dump_kb) dump_tile(v, a, b);
+    } else {
+      fold<16 * part / KPB, 16 * (part + 1) / KPB>(acc[a][b], v, scale);
     }
-    // Main loop: passes of NBUF whole stages, each with a successor and a stage to prefetch, so the ring slot
-    // of every stage is a compile-time constant: LDS addresses are immediates and the accumulators never move.
-    int t = 0;
-    for (; t + 2 * NBUF - 1 <= tl; t += NBUF) {
-      // The instruction arbiter favours the oldest wave of a SIMD, so co-resident waves would finish one after
-      // the other and leave the SIMD to a single wave at the end.  Each wave therefore lowers its own priority
-      // as it advances: whoever is ahead yields, and the waves of a SIMD reach the end together.
-      if (4 * t < nstages) __builtin_amdgcn_s_setprio(3);
-      else if (2 * t < nstages) __builtin_amdgcn_s_setprio(2);
-      else if (4 * t < 3 * nstages) __builtin_amdgcn_s_setprio(1);
-      else __builtin_amdgcn_s_setprio(0);
+  };
+  // MFMA number js of the chain of unit i of a stage (quantization block i / NTILE, sub-block i % NTILE) into dst
+  auto chain_step = [&](int i, int js, v16i& dst) __attribute__((always_inline)) {
+    const int kb = i / NTILE, a = (i % NTILE) / WN, b = (i % NTILE) % WN;
+    dst = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[kb * KPB + js][b], fa[kb * KPB + js][a], js == 0 ? zero16 : dst, 0, 0, 0);
+  };
+  auto chain = [&](int i, v16i& dst) __attribute__((always_inline)) {
 #pragma unroll
-      for (int u = 0; u < NBUF; ++u)
-        run_stage(t + u, u, (u + 1) % NBUF, whole_tag, std::true_type(), std::true_type(), std::true_type(), std::true_type());
-    }
-    // The last R = 1 .. 2*NBUF-1 stages as straight-line code per R, so that their flags are constants too.
-    __builtin_amdgcn_s_setprio(0);
-    auto run_tail = [&](auto r_tag) __attribute__((always_inline)) {
-      constexpr int R = decltype(r_tag)::value;
-      static_for<0, R>([&](auto i_tag) __attribute__((always_inline)) {
-        constexpr int i = decltype(i_tag)::value;
-        run_stage(t + i, i % NBUF, (i + 1) % NBUF, whole_tag, std::integral_constant<bool, (i + 1 < R)>(),
-                  std::integral_constant<bool, (i + AHEAD < R)>(), std::integral_constant<bool, (i + 1 + AHEAD < R)>(),
-                  std::integral_constant<bool, (i + 3 < R)>());
-      });
-    };
-    const int R = tl - t + 1;
-    static_for<1, 2 * NBUF>([&](auto r_tag) __attribute__((always_inline)) {
-      if (R == decltype(r_tag)::value) run_tail(r_tag);
+    for (int js = 0; js < KPB; ++js) chain_step(i, js, dst);
+  };
+  // One unit's fold with the next unit's chain woven in: each MFMA (32 cycles of the matrix pipe) is followed
+  // by 32/KPB vector instructions (4 cycles each), so a single wave keeps both pipes busy and never waits to
+  // issue the next MFMA of a chain.  next < 0: fold only.
+  auto fold_and_chain = [&](int t, int kb, int a, int b, v16i& cur, float scale, int next, v16i& nxt) __attribute__((always_inline)) {
+    static_for<0, KPB>([&](auto js) __attribute__((always_inline)) {
+      if (next >= 0) chain_step(next, decltype(js)::value, nxt);
+      __builtin_amdgcn_sched_barrier(0);
+      fold_or_dump(t, kb, a, b, cur, scale, js);
+      __builtin_amdgcn_sched_barrier(0);
     });
-  } else {
-    // ---- B = 64 / 128: the INT32 tiles accumulate over KPB K steps inside the MFMA, then are folded.
-    // One stage (STEPS K steps) out of buffer `buf`.
-    auto compute = [&](int s, int buf, auto steps_tag) __attribute__((always_inline)) {
-      constexpr int STEPS = decltype(steps_tag)::value;
-      const int8_t* ta = tile_buf(buf);
-      const int8_t* tb = ta + A_BYTES;
-      // this stage's scales were fetched during the previous stage; fetch the next stage's now
-      rotate_scales();
-      if (s + 1 < nstages) load_scales(s + 1);
-      float (&sa)[WM][SPS] = sa_c;
-      float (&sb)[WN][SPS] = sb_c;
+  };
+  // Stage t out of ring slot `slot`; on entry the chain of its first unit is in flight in vi[0].  With a next
+  // stage (in slot `nslot`) the chain of that stage's first unit is in flight in vi[0] on return.
+  //   keep: stage t + AHEAD exists (its loads may stay in flight over the barrier);
+  //   more: stage t + 1 + AHEAD exists and is prefetched into the slot this stage frees;
+  //   far:  stage t + 3 exists (its scales are requested now).
+  // The flags are compile-time constants everywhere but in the odd first stage.
+  auto run_stage = [&](int t, int slot, int nslot, auto steps_tag, auto has_next, auto keep, auto more, auto far) __attribute__((always_inline)) {
+    constexpr int NT = (decltype(steps_tag)::value / KPB) * NTILE;
 #pragma unroll
-      for (int j = 0; j < STEPS; ++j) {
-        v4i fa[WM], fb[WN];
-#pragma unroll
-        for (int a = 0; a < WM; ++a) fa[a] = addrA.read(ta, a, j);
-#pragma unroll
-        for (int b = 0; b < WN; ++b) fb[b] = addrB.read(tb, b, j);
-#pragma unroll
-        for (int t = 0; t < NTILE; ++t)
-          vchain[t] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[t % WN], fa[t / WN], (j % KPB == 0) ? zero16 : vchain[t], 0, 0, 0);
-        if ((j + 1) % KPB == 0) {  // end of a quantization block along K (a stage holds whole blocks)
-#pragma unroll
-          for (int t = 0; t < NTILE; ++t) {
-            if (DUMP) {
-              if ((s * SPS + j) / KPB == g.dump_kb) dump_tile(vchain[t], t / WN, t % WN);
-            } else {
-              fold(acc[t / WN][t % WN], vchain[t], sa[t / WN][j] * sb[t % WN][j]);
-            }
-          }
-        }
-      }
-    };
-    auto compute_partial = [&](int s, int buf) __attribute__((always_inline)) {
-      const int rem = nsteps - s * SPS;
-      if constexpr (SPS >= 4 && KPB <= 2) { if (rem == 2) compute(s, buf, std::integral_constant<int, 2>()); }
-    };
-    load_scales(0);
-#pragma unroll
-    for (int i = 0; i < AHEAD; ++i)
-      if (i < nstages) issue_at(i * KC, i, false);
-    wait_loads(nstages >= AHEAD);
-    int s = 0;
-    // inside this loop stage s + NBUF + AHEAD - 1 .. exist for every issue, and every computed stage is whole
-    for (; s + NBUF <= nwhole && s + NBUF + AHEAD - 1 < nstages; s += NBUF) {
-#pragma unroll
-      for (int u = 0; u < NBUF; ++u) {
-        issue_at((s + u + AHEAD) * KC, (u + AHEAD) % NBUF, false);
-        compute(s + u, u, whole_tag);
-        wait_loads(true);
+    for (int i = 0; i < NT; ++i) {
+      const int kb = i / NTILE, a = (i % NTILE) / WN, b = (i % NTILE) % WN, cur = i & 1;
+      const float scale = sa_c[a][kb] * sb_c[b][kb];
+      if (i + 1 < NT) {
+        fold_and_chain(t, kb, a, b, vi[cur], scale, i + 1, vi[cur ^ 1]);
+      } else if (has_next) {
+        advance_scales(far, NKB);  // before the barrier: the wait there covers the scalar loads
+        wait_loads(keep);
+        if (more) issue_whole(t + 1 + AHEAD, slot);
+        read_frags(nslot);
+        fold_and_chain(t, kb, a, b, vi[cur], scale, -1, vi[cur]);
+        chain(0, vi[0]);
+      } else {
+        fold_and_chain(t, kb, a, b, vi[cur], scale, -1, vi[cur]);
       }
     }
-    for (int buf = s % NBUF; s < nstages; ++s, buf = (buf + 1 == NBUF ? 0 : buf + 1)) {
-      const bool more = s + AHEAD < nstages;
-      if (more) issue_at((s + AHEAD) * KC, (buf + AHEAD) % NBUF, false);
-      if (s < nwhole) compute(s, buf, whole_tag);
-      else compute_partial(s, buf);
-      wait_loads(more);
-    }
+  };
+
+  static_assert(NBUF >= 3, "a prefetched stage implies the stage whose scales are requested");
+  advance_scales(true, (rem ? rem : SPS) / KPB);
+  advance_scales(t0 + 1 <= tl, NKB);
+#pragma unroll
+  for (int i = 0; i < AHEAD; ++i)
+    if (t0 + i <= tl) issue(t0 + i, slot_of(t0 + i));
+  wait_loads(t0 + AHEAD - 1 <= tl);
+  if (t0 + AHEAD <= tl) issue(t0 + AHEAD, slot_of(t0 + AHEAD));
+  advance_scales(t0 + 2 <= tl, NKB);
+  read_frags(slot_of(t0));
+  chain(0, vi[0]);
+  if (rem) {  // the odd first stage: 1 .. SPS-1 K steps, an odd tile count flips the rotation, hence vi[0] again
+    const bool has_next = tl >= 0, keep = AHEAD - 1 <= tl, more = AHEAD <= tl, far = 2 <= tl;
+    if constexpr (SPS >= 2 && KPB == 1) { if (rem == 1) run_stage(-1, NBUF - 1, 0, std::integral_constant<int, 1>(), has_next, keep, more, far); }
+    if constexpr (SPS >= 4 && KPB <= 2) { if (rem == 2) run_stage(-1, NBUF - 1, 0, std::integral_constant<int, 2>(), has_next, keep, more, far); }
+    if constexpr (SPS >= 4 && KPB == 1) { if (rem == 3) run_stage(-1, NBUF - 1, 0, std::integral_constant<int, 3>(), has_next, keep, more, far); }
   }
+  // Main loop: passes of NBUF whole stages, each with a successor and a stage to prefetch, so the ring slot
+  // of every stage is a compile-time constant: LDS addresses are immediates and the accumulators never move.
+  int t = 0;
+  for (; t + 2 * NBUF - 1 <= tl; t += NBUF) {
+    // The instruction arbiter favours the oldest wave of a SIMD, so co-resident waves would finish one after
+    // the other and leave the SIMD to a single wave at the end.  Each wave therefore lowers its own priority
+    // as it advances: whoever is ahead yields, and the waves of a SIMD reach the end together.
+    if (4 * t < nstages) __builtin_amdgcn_s_setprio(3);
+    else if (2 * t < nstages) __builtin_amdgcn_s_setprio(2);
+    else if (4 * t < 3 * nstages) __builtin_amdgcn_s_setprio(1);
+    else __builtin_amdgcn_s_setprio(0);
+#pragma unroll
+    for (int u = 0; u < NBUF; ++u)
+      run_stage(t + u, u, (u + 1) % NBUF, whole_tag, std::true_type(), std::true_type(), std::true_type(), std::true_type());
+  }
+  // The last R = 1 .. 2*NBUF-1 stages as straight-line code per R, so that their flags are constants too.
+  __builtin_amdgcn_s_setprio(0);
+  auto run_tail = [&](auto r_tag) __attribute__((always_inline)) {
+    constexpr int R = decltype(r_tag)::value;
+    static_for<0, R>([&](auto i_tag) __attribute__((always_inline)) {
+      constexpr int i = decltype(i_tag)::value;
+      run_stage(t + i, i % NBUF, (i + 1) % NBUF, whole_tag, std::integral_constant<bool, (i + 1 < R)>(),
+                std::integral_constant<bool, (i + AHEAD < R)>(), std::integral_constant<bool, (i + 1 + AHEAD < R)>(),
+                std::integral_constant<bool, (i + 3 < R)>());
+    });
+  };
+  const int R = tl - t + 1;
+  static_for<1, 2 * NBUF>([&](auto r_tag) __attribute__((always_inline)) {
+    if (R == decltype(r_tag)::value) run_tail(r_tag);
+  });
   if (DUMP) return;
 
   // ---- epilogue: optional FP32 store, per-block max-abs, Eq. 1, packed INT8 store
@@ -623,9 +584,10 @@ __global__ void __launch_bounds__(64 * WGM * WGN, WMIN) gemm_kernel(const GemmAr
 template <int B, int WM, int WN, int WGM, int WGN, bool AK, bool BK, bool DUMP>
 static void launch_cfg(const GemmArgs& a, hipStream_t st) {
   constexpr int TM = 32 * WM * WGM, TN = 32 * WN * WGN;
-  // resident waves per SIMD the register allocation has to allow: 3 for the 2x2 wave tile at B = 32 (three
-  // 128x128 workgroups share a compute unit), 1 for the 1x3 wave tiles (one workgroup per compute unit)
-  constexpr int WMIN = (WM * WN >= 4) ? (B == 32 ? 3 : 2) : (WGM * WGN > 4 ? 3 : 4);
+  // resident waves per SIMD the register allocation has to allow: 3 for the 2x2 wave tile (three
+  // 128x128 workgroups share a compute unit), the waves of the one workgroup per compute unit for the big
+  // workgroups (2 for eight waves, 3 for nine or twelve), 4 for the 64x64 tiles
+  constexpr int WMIN = (WM * WN >= 4) ? 3 : (WGM * WGN > 8 ? 3 : (WGM * WGN > 4 ? 2 : 4));
   const int tiles = ((a.M + TM - 1) / TM) * ((a.Nn + TN - 1) / TN);
   hipLaunchKernelGGL((gemm_kernel<B, WM, WN, WGM, WGN, AK, BK, DUMP, WMIN>), dim3(tiles), dim3(64 * WGM * WGN), 0, st, a);
 }
@@ -638,6 +600,7 @@ static void launch_cfg(const GemmArgs& a, hipStream_t st) {
 //   128x96   twelve waves of one sub-block } one workgroup per compute unit, for outputs with too few
 //    96x96   nine waves of one sub-block   } 128x128 tiles to fill 256 compute units evenly;
 //    64x64   four waves of one sub-block.
+static int g_forced_shape = 0;  // test hook, see jf_debug_set_gemm_shape
 struct ShapeCost {
   int64_t cycles;
 };
@@ -650,20 +613,12 @@ static ShapeCost shape_cost(const GemmArgs& a, int tm, int tn, int waves, int ti
   const int64_t stage = q * (int64_t)(tm + tn) * a.K / 28;           // ~28 bytes per cycle of L2 -> LDS per compute unit
   return {valu > stage ? valu : stage};
 }
-static int g_forced_shape = 0;  // test hook, see jf_debug_set_gemm_shape
-static ShapeCost shape_cost(const GemmArgs& a, int tm, int tn, int tiles_per_wave, bool single_wave_per_simd) {
-  const int64_t n_wg = (int64_t)((a.M + tm - 1) / tm) * ((a.Nn + tn - 1) / tn);
-  const int64_t q = (n_wg + 255) / 256;                              // workgroups on the busiest compute unit
-  int64_t valu = q * tiles_per_wave * (a.K / 32) * 140;              // ~35 vector instructions of 4 cycles per sub-block and K step
-  if (single_wave_per_simd && q == 1) valu += valu / 7;              // nothing else to hide this wave's stalls
-  const int64_t stage = q * (int64_t)(tm + tn) * a.K / 20;           // ~20 bytes per cycle of L2 -> LDS per compute unit
-  return {valu > stage ? valu : stage};
-}
-
 template <int B, bool AK, bool BK, bool DUMP>
 static void launch_shape(const GemmArgs& a, hipStream_t st) {
   if constexpr (B == 128) {
-    launch_cfg<B, 2, 2, 2, 2, AK, BK, DUMP>(a, st);
+    // 128x128 tile, eight waves of 2x1 sub-blocks: two waves per SIMD with one workgroup per compute unit, so
+    // that the MFMA chains of one wave run under the folds of the other
+    launch_cfg<B, 2, 1, 2, 4, AK, BK, DUMP>(a, st);
   } else if constexpr (B == 64) {
     const bool big = g_forced_shape ? g_forced_shape != 4
                                     : shape_cost(a, 128, 128, 4, 4).cycles <= shape_cost(a, 64, 64, 4, 1).cycles;

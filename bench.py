@@ -42,6 +42,13 @@ def parse_args():
     ap.add_argument("--event-every", type=int, default=8,
                     help="bracket the GEMM launches with HIP events on every n-th timed step only")
     ap.add_argument("--graph", action="store_true", help="also time the step replayed from a captured HIP graph")
+    ap.add_argument("--sweep", action="store_true",
+                    help="instead of the default step: time fwd/dgrad/wgrad over the large-GEMM sweep (config 5: "
+                         "M=N=K in {2048,4096,8192} and tokens 16384 x LLaMA-7B linears, block 32/64/128)")
+    ap.add_argument("--sweep-blocks", type=str, default="32,64,128")
+    ap.add_argument("--sweep-shape", type=int, default=0, help="force a GEMM tile shape in the sweep (test hook)")
+    ap.add_argument("--sweep-only", type=str, default="", help="run one sweep shape only, as tokens,in,out")
+    ap.add_argument("--sweep-max-dim", type=int, default=16384, help="skip sweep shapes with a larger dimension")
     return ap.parse_args()
 
 
@@ -89,6 +96,93 @@ def cpu_baseline(args, N, C, D, block):
     }
 
 
+SWEEP_SHAPES = [  # (tokens N, in C, out D)
+    (2048, 2048, 2048), (4096, 4096, 4096), (8192, 8192, 8192),
+    (16384, 4096, 4096), (16384, 4096, 11008), (16384, 11008, 4096),
+]
+
+
+def sweep(args):
+    """Large-GEMM sweep (config 5): kernel time of each product from HIP events around back-to-back launches.
+
+    Values are N(0,1) with 0.5 % outlier columns x50, drawn on the GPU (torch.randn, seeded) because the largest
+    tensors have 1.8e8 elements; they are quantized by jf_quantize_block.  One JSON line with one record per
+    (shape, block)."""
+    import torch
+
+    import paper_2403_12422_amd as jf
+
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(240312422 + 5)
+
+    def draw(r, c):
+        x = torch.randn((r, c), generator=gen, device=dev, dtype=torch.float32)
+        n_out = max(1, round(0.005 * c))
+        cols = torch.randperm(c, generator=gen, device=dev)[:n_out]
+        x[:, cols] *= 50.0
+        return x
+
+    def time_ms(fn, ops):
+        fn()
+        torch.cuda.synchronize()
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record()
+        fn()
+        e1.record()
+        torch.cuda.synchronize()
+        one = max(e0.elapsed_time(e1), 1e-3)
+        reps = int(min(200, max(5, 60.0 / one)))          # about 60 ms of kernel time per measurement
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    jf.jf_debug_set_gemm_shape(args.sweep_shape)
+    records = []
+    blocks = [int(b) for b in args.sweep_blocks.split(",")]
+    shapes = [tuple(int(v) for v in args.sweep_only.split(","))] if args.sweep_only else SWEEP_SHAPES
+    for (N, C, D) in shapes:
+        if max(N, C, D) > args.sweep_max_dim:
+            continue
+        Xf, Wf, Gf = draw(N, C), draw(D, C), draw(N, D)
+        for B in blocks:
+            Xq, SX = jf.jf_quantize_block(Xf, B)
+            Wq, SW = jf.jf_quantize_block(Wf, B)
+            Gq, SG = jf.jf_quantize_block(Gf, B)
+            i8 = lambda r, c: torch.empty((r, c), dtype=torch.int8, device=dev)
+            sc = lambda r, c: torch.empty((r // B, c // B), dtype=torch.float32, device=dev)
+            oY, odX, odW = (i8(N, D), sc(N, D), None), (i8(N, C), sc(N, C), None), (i8(D, C), sc(D, C), None)
+            ops = 2.0 * N * C * D
+            ms = {
+                "fwd": time_ms(lambda: jf.jf_linear_fwd(Xq, SX, Wq, SW, B, out=oY), ops),
+                "dgrad": time_ms(lambda: jf.jf_linear_dgrad(Gq, SG, Wq, SW, B, out=odX), ops),
+                "wgrad": time_ms(lambda: jf.jf_linear_wgrad(Gq, SG, Xq, SX, B, out=odW), ops),
+            }
+            tops = {k: ops / (v * 1e-3) * 1e-12 for k, v in ms.items()}
+            total = 3 * ops / (sum(ms.values()) * 1e-3) * 1e-12
+            rec = {"tokens": N, "in": C, "out": D, "block": B,
+                   "ms": {k: round(v, 4) for k, v in ms.items()},
+                   "TOPS": {k: round(v, 1) for k, v in tops.items()},
+                   "TOPS_fwd_dgrad_wgrad": round(total, 1), "frac_int8_mfma_peak": round(total / INT8_MFMA_PEAK_TOPS, 4)}
+            records.append(rec)
+            print(f"# sweep {N}x{C}->{D} block {B}: " + ", ".join(f"{k} {ms[k]:.3f} ms {tops[k]:.0f} TOP/s" for k in ms)
+                  + f" | all three {total:.0f} TOP/s ({100 * total / INT8_MFMA_PEAK_TOPS:.1f} % of INT8 MFMA peak)",
+                  file=sys.stderr, flush=True)
+            del Xq, Wq, Gq, oY, odX, odW
+        del Xf, Wf, Gf
+        torch.cuda.empty_cache()
+    best = max(records, key=lambda r: r["TOPS_fwd_dgrad_wgrad"])
+    print(json.dumps({
+        "metric": "per-block INT8 linear TOPS (fwd+dgrad+wgrad), large-GEMM sweep", "unit": "TOPS",
+        "value": best["TOPS_fwd_dgrad_wgrad"], "n_gpus": 1, "dtype": "int8", "data": "synthetic",
+        "config": {"workload": "config 5: large-GEMM sweep; `value` is the best (shape, block) record"},
+        "peak_TOPS": INT8_MFMA_PEAK_TOPS, "sweep": records}), flush=True)
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -107,6 +201,9 @@ def main():
     jf.load_library()
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.sweep:
+        sweep(args)
+        return
     N, C, D, B = args.tokens, args.in_features, args.out_features, args.block
 
     # ---- synthetic batch (config 2 recipe), resident in HBM before the timed region

@@ -1,0 +1,4 @@
+// gemm_kernel instances of the dgrad product at block size 128 (a translation unit of its own for build time).
+#include "jf_gemm_kernel.hpp"
+
+JF_GEMM_INSTANCE(launch_gemm_dgrad_b128, 128, true, false)

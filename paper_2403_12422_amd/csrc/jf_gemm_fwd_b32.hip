@@ -1,0 +1,4 @@
+// gemm_kernel instances of the fwd product at block size 32 (a translation unit of its own for build time).
+#include "jf_gemm_kernel.hpp"
+
+JF_GEMM_INSTANCE(launch_gemm_fwd_b32, 32, true, true)

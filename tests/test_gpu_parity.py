@@ -213,13 +213,22 @@ def _check_sampled(name, got, A, SA, Bm, SB, block, g, nblk=48):
         assert_scales_close(s[p, c], os_[n], name)
         nbad += assert_codes_close(q[sl], oq[n], name, prequant=o32[n], scales=np.full((block, block), os_[n]))
     assert nbad <= 1e-3 * len(bp) * block * block
-    # properties that hold everywhere: every non-zero block reaches +-127, scale = amax/127 of the FP32 output
-    amax = block_amax(f, block)
-    np.testing.assert_allclose(s, amax / np.float32(127), rtol=1e-6)
-    qa = block_amax(q.astype(np.float32), block)
-    assert np.all(qa[amax > 0] == 127)
-    err = np.abs(q.astype(np.float64) * expand(s.astype(np.float64), block) - f)
-    assert np.all(err <= 0.5 * expand(s.astype(np.float64), block) * (1 + 1e-5))
+    # properties that hold everywhere: every non-zero block reaches +-127, scale = amax/127 of the FP32 output,
+    # the half-step error bound.  Outputs above 2^25 elements are checked on eight random bands of block rows.
+    if q.size > (1 << 25):
+        rows_per_band = max(block, (1 << 22) // Nn // block * block)
+        starts = g.choice(M // rows_per_band, size=min(8, M // rows_per_band), replace=False) * rows_per_band
+        bands = [(int(r0), int(r0) + rows_per_band) for r0 in starts]
+    else:
+        bands = [(0, M)]
+    for r0, r1 in bands:
+        fb, qb, sb = f[r0:r1], q[r0:r1], s[r0 // block:r1 // block]
+        amax = block_amax(fb, block)
+        np.testing.assert_allclose(sb, amax / np.float32(127), rtol=1e-6)
+        qa = block_amax(qb.astype(np.float32), block)
+        assert np.all(qa[amax > 0] == 127)
+        se = expand(sb.astype(np.float64), block)
+        assert np.all(np.abs(qb.astype(np.float64) * se - fb) <= 0.5 * se * (1 + 1e-5))
     say(f"  {name}: {len(bp)} sampled blocks ok, {nbad} tie codes")
 
 
@@ -306,3 +315,38 @@ def test_layernorm_fwd_bwd(block, N, C):
     # run-to-run bit stability of the column reductions
     dX2, SdX2, dgam2, dbet2 = jf.jf_layernorm_q_bwd(Gd, SGd, Xd, SXd, gd, dev(omean), dev(orstd), block)
     assert torch.equal(dgam, dgam2) and torch.equal(dbet, dbet2) and torch.equal(dX, dX2)
+
+
+# --------------------------------------------------------------------------- large-GEMM sweep (config 5)
+# Every shape of the sweep and every block size appear at least once; the full cross product would only
+# repeat the same code paths.  Each product is checked on sampled output blocks (each over the full K, FP32
+# accumulator bit-exact) and on properties of the whole output.
+_SWEEP_CASES = [
+    (2048, 2048, 2048, 32), (2048, 2048, 2048, 64), (2048, 2048, 2048, 128),
+    (4096, 4096, 4096, 32), (4096, 4096, 4096, 64), (4096, 4096, 4096, 128),
+    (8192, 8192, 8192, 32), (8192, 8192, 8192, 128),
+    (16384, 4096, 4096, 64), (16384, 4096, 11008, 128), (16384, 11008, 4096, 32),
+]
+
+
+@pytest.mark.parametrize("N,C,D,block", _SWEEP_CASES)
+def test_linear_config5_sweep_sampled(N, C, D, block):
+    """Large-GEMM sweep shapes at full size: N(0,1) data with 0.5 % outlier columns x50, all three products."""
+    say(f"linear sweep N={N} C={C} D={D} block={block}: drawing and quantizing inputs")
+    X, W, dY = workloads.linear_layer(5000 + N // 64 + C // 32 + block, N, C, D, act_std=1.0, w_std=1.0, grad_std=1.0,
+                                      outlier_fraction=0.005, outlier_factor=50.0)
+    (X, SX), (W, SW), (dY, SdY) = (oracle.quantize_block(a, block) for a in (X, W, dY))
+    Xd, SXd, Wd, SWd, dYd, SdYd = map(dev, (X, SX, W, SW, dY, SdY))
+    g = workloads.rng(5100 + block)
+    nblk = 8
+    say("  forward")
+    _check_sampled("fwd", jf.jf_linear_fwd(Xd, SXd, Wd, SWd, block, want_f32=True), X, SX, W, SW, block, g, nblk)
+    say("  dgrad")
+    WT, SWT = oracle.transpose(W, SW, block)
+    _check_sampled("dgrad", jf.jf_linear_dgrad(dYd, SdYd, Wd, SWd, block, want_f32=True), dY, SdY, WT, SWT, block, g, nblk)
+    del WT, SWT
+    say("  wgrad")
+    dYT, SdYT = oracle.transpose(dY, SdY, block)
+    XT, SXT = oracle.transpose(X, SX, block)
+    _check_sampled("wgrad", jf.jf_linear_wgrad(dYd, SdYd, Xd, SXd, block, want_f32=True), dYT, SdYT, XT, SXT, block, g, nblk)
+    torch.cuda.empty_cache()

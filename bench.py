@@ -41,6 +41,8 @@ def parse_args():
                     help="also launch plain 256 MiB device copies, the reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE")
     ap.add_argument("--event-every", type=int, default=8,
                     help="bracket the GEMM launches with HIP events on every n-th timed step only")
+    ap.add_argument("--no-hbm-sized-ops", action="store_true",
+                    help="skip timing GELU / LayerNorm / quantize on tensors too large for the last-level cache")
     ap.add_argument("--graph", action="store_true", help="also time the step replayed from a captured HIP graph")
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the default step: time fwd/dgrad/wgrad over the large-GEMM sweep (config 5: "
@@ -329,6 +331,53 @@ def main():
         memops[name] = {"ms": round(ms, 5), "GB/s": round(nbytes / (ms * 1e-3) * 1e-9, 1),
                         "frac_hbm_peak": round(nbytes / (ms * 1e-3) * 1e-9 / HBM_PEAK_GBPS, 4)}
 
+    # The tensors above (6-38 MB) fit the 256 MB last-level cache, so those figures are cache/latency figures.
+    # The HBM fraction of the same kernels is measured on tensors of 64x (GELU) / 256x (LayerNorm) the token
+    # count, 0.8 GB per operand, which no cache holds; values are random codes and scales drawn on the GPU.
+    memops_hbm = None
+    if not args.no_hbm_sized_ops:
+        memops_hbm = {}
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(240312422 + 3)
+        ri8 = lambda r, c: torch.randint(-127, 128, (r, c), generator=gen, device=dev, dtype=torch.int8)
+        rsc = lambda r, c, m: torch.rand((r // B, c // B), generator=gen, device=dev, dtype=torch.float32) * m + 1e-3 * m
+        NG, NL = 64 * N, 256 * N
+        xg, sxg, gg, sgg = ri8(NG, D), rsc(NG, D, 0.06), ri8(NG, D), rsc(NG, D, 3e-5)
+        yg, syg = i8(NG, D), sc(NG, D)
+        big = {
+            "gelu_fwd": (lambda: jf.jf_gelu_q(xg, sxg, B, out=(yg, syg)), NG * D * (2 + 2 * sb)),
+            "gelu_bwd": (lambda: jf.jf_gelu_q_bwd(gg, sgg, xg, sxg, B, out=(yg, syg)), NG * D * (3 + 3 * sb)),
+        }
+        for name, (fn, nbytes) in big.items():
+            ms = op_ms(fn, reps=4, replays=3)
+            memops_hbm[name] = {"tokens": NG, "ms": round(ms, 4), "GB/s": round(nbytes / (ms * 1e-3) * 1e-9, 1),
+                                "frac_hbm_peak": round(nbytes / (ms * 1e-3) * 1e-9 / HBM_PEAK_GBPS, 4)}
+        del xg, sxg, gg, sgg, yg, syg
+        torch.cuda.empty_cache()
+        xl, sxl, gl, sgl = ri8(NL, C), rsc(NL, C, 0.05), ri8(NL, C), rsc(NL, C, 3e-5)
+        yl, syl, ml, rl = i8(NL, C), sc(NL, C), f32(NL), f32(NL)
+        wsl = torch.empty((max(16, jf.jf_workspace_bytes(7, NL, C, 0, B)),), dtype=torch.uint8, device=dev)
+        jf.jf_layernorm_q(xl, sxl, gamma, beta, 1e-5, B, out=(yl, syl, ml, rl))
+        big = {
+            "layernorm_fwd": (lambda: jf.jf_layernorm_q(xl, sxl, gamma, beta, 1e-5, B, out=(yl, syl, ml, rl)),
+                              NL * C * (2 + 2 * sb) + 8 * NL + 8 * C),
+            "layernorm_bwd": (lambda: jf.jf_layernorm_q_bwd(gl, sgl, xl, sxl, gamma, ml, rl, B, workspace=wsl,
+                                                            out=(yl, syl, dgamma, dbeta)),
+                              NL * C * (3 + 3 * sb) + 8 * NL + 12 * C),
+        }
+        for name, (fn, nbytes) in big.items():
+            ms = op_ms(fn, reps=4, replays=3)
+            memops_hbm[name] = {"tokens": NL, "ms": round(ms, 4), "GB/s": round(nbytes / (ms * 1e-3) * 1e-9, 1),
+                                "frac_hbm_peak": round(nbytes / (ms * 1e-3) * 1e-9 / HBM_PEAK_GBPS, 4)}
+        xq = torch.randn((NL // 4, D), generator=gen, device=dev, dtype=torch.float32)
+        oq, osq = i8(NL // 4, D), sc(NL // 4, D)
+        ms = op_ms(lambda: jf.jf_quantize_block(xq, B, out=(oq, osq)), reps=4, replays=3)
+        nbytes = (NL // 4) * D * (5 + sb)
+        memops_hbm["quantize_f32"] = {"tokens": NL // 4, "ms": round(ms, 4), "GB/s": round(nbytes / (ms * 1e-3) * 1e-9, 1),
+                                      "frac_hbm_peak": round(nbytes / (ms * 1e-3) * 1e-9 / HBM_PEAK_GBPS, 4)}
+        del xl, sxl, gl, sgl, yl, syl, ml, rl, wsl, xq, oq, osq
+        torch.cuda.empty_cache()
+
     # HBM traffic of the GEMM kernel: measured offline with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see the
     # summary named in the file) and valid for the default workload only
     traffic = None
@@ -368,6 +417,7 @@ def main():
             "linear_only_TOPS": round(6.0 * N * C * D / (sum(per_gemm) * 1e-3) * 1e-12, 2),
         },
         "memory_bound_ops": memops,
+        "memory_bound_ops_hbm_sized": memops_hbm,
         "paper_context": "paper reports ratios only: 1.42x transformer-layer speedup, 1.49x activation memory vs FP16 on RTX 4090",
     }
     if graph_ms is not None:

@@ -26,8 +26,7 @@ extern "C" size_t jf_workspace_bytes(int32_t op, int64_t N, int64_t C, int64_t D
   if (!jf::valid_block(block) || N <= 0 || C <= 0) return 0;
   switch (op) {
     case JF_OP_LAYERNORM_BWD:
-      // one row of (dgamma, dbeta) column partials per wave: four per workgroup of `block` rows
-      return (size_t)(N / block) * 4 * 2 * (size_t)C * sizeof(float);
+      return (size_t)jf::ln_bwd_partial_rows(N, C, block) * 2 * (size_t)C * sizeof(float);
     default:
       return 0;
   }

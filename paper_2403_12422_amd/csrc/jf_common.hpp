@@ -29,6 +29,13 @@ inline bool aligned4(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 3
 inline bool valid_block(int32_t b) { return b == 32 || b == 64 || b == 128; }
 // Dimensions are kept below 2^24 so that every index fits an int32 after
 // division by the block size and element offsets fit 48 bits.
+// Rows of dgamma | dbeta partial sums that the LayerNorm backward kernels leave in the workspace.  Up to 2048
+// columns a workgroup walks over the row blocks it owns and leaves one row (at most two workgroups per compute
+// unit); wider rows use one workgroup per row block, which leaves four.
+inline int64_t ln_bwd_partial_rows(int64_t N, int64_t C, int32_t block) {
+  if (C > 2048) return (N / block) * 4;
+  return N / block < 512 ? N / block : 512;
+}
 inline bool valid_dim(int64_t d, int32_t block) { return d > 0 && d <= (int64_t(1) << 24) && d % block == 0; }
 
 // -------------------------------------------------------------- device side

@@ -346,13 +346,207 @@ __global__ void __launch_bounds__(1024) layernorm_fwd_kernel(const int8_t* __res
   }
 }
 
-// LayerNorm backward.  Sixteen waves per workgroup, RW = B/16 rows per wave.  Sweep 1: per row
+// LayerNorm backward.  Eight waves per workgroup, RW = B/8 rows per wave, walked one row at a time (the next
+// row's codes are requested before the current row is worked on).  A workgroup walks over the row blocks
+// blockIdx.x, blockIdx.x + gridDim.x, ... and leaves ONE row of dgamma | dbeta partial sums in the
+// workspace.  With ghat = g gamma and xhat = (x - mean) rstd, dx = rstd y where
+//   y = ghat - mean_C(ghat) - xhat mean_C(ghat xhat).
+// Pass A, per row: the two row means (wave reduction), the running column sums of g*xhat and g, and the
+// max-abs of dx per chunk column; the row means go to LDS.  After the block max-abs is known, pass B reads
+// the codes again (they are in L2), recomputes y and stores the codes.  The column sums stay in registers
+// over all row blocks of the workgroup and are folded over the waves once, at the end, in a fixed order
+// (wave w into LDS row w % 4 in round w / 4), so results are bit-stable.  NIT <= 2 (C <= 2048).
+template <int B, int NIT>
+__global__ void __launch_bounds__(512, NIT == 1 ? 3 : 2) layernorm_bwd_kernel(
+    const int8_t* __restrict__ G, const float* __restrict__ SG, const int8_t* __restrict__ X, const float* __restrict__ SX,
+    const float* __restrict__ gamma, const float* __restrict__ mean_in, const float* __restrict__ rstd_in, int rows,
+    int cols, int8_t* __restrict__ dX, float* __restrict__ SdX, float* __restrict__ partials) {
+  constexpr int NW = 8, RW = B / NW;
+  extern __shared__ float s_dyn[];        // [NW][C/32] block max-abs | [B][2] row means | [4][2][C] column sums
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lc = cols / B, nchunks = cols / 16, ngran = cols / 32;
+  float* s_amax = s_dyn;
+  float* s_q = s_dyn + NW * ngran;
+  float* s_col = s_q + 2 * B;
+  const float inv_cols = 1.0f / (float)cols;
+
+  bool ok[NIT];
+  float gm[NIT][16], cgs[NIT][16], cbs[NIT][16];
+#pragma unroll
+  for (int it = 0; it < NIT; ++it) {
+    ok[it] = lane + 64 * it < nchunks;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) gm[it][e] = cgs[it][e] = cbs[it][e] = 0.0f;
+    if (ok[it]) load16f(gamma + 16 * (lane + 64 * it), gm[it]);
+  }
+  auto load_row = [&](const int8_t* base, int row, uint4 (&v)[NIT]) {
+#pragma unroll
+    for (int it = 0; it < NIT; ++it)
+      v[it] = ok[it] ? *reinterpret_cast<const uint4*>(base + (int64_t)row * cols + 16 * (lane + 64 * it)) : make_uint4(0, 0, 0, 0);
+  };
+
+  for (int bi = blockIdx.x; bi < rows / B; bi += gridDim.x) {
+    const int r0 = bi * B + wave * RW;
+    float sx[NIT], sgv[NIT], mloc[NIT];
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+      const int c = lane + 64 * it;
+      sx[it] = ok[it] ? SX[(int64_t)bi * lc + (16 * c) / B] : 0.0f;
+      sgv[it] = ok[it] ? SG[(int64_t)bi * lc + (16 * c) / B] : 0.0f;
+      mloc[it] = 0.0f;
+    }
+
+    // ---- pass A
+    uint4 nx[NIT], ng[NIT];
+    load_row(X, r0, nx);
+    load_row(G, r0, ng);
+#pragma unroll 1
+    for (int r = 0; r < RW; ++r) {
+      uint4 cx[NIT], cgc[NIT];
+#pragma unroll
+      for (int it = 0; it < NIT; ++it) { cx[it] = nx[it]; cgc[it] = ng[it]; }
+      if (r + 1 < RW) {
+        load_row(X, r0 + r + 1, nx);
+        load_row(G, r0 + r + 1, ng);
+      }
+      const float mu = mean_in[r0 + r], rs = rstd_in[r0 + r];
+      const float mrs = -mu * rs;
+      float m1 = 0.0f, m2 = 0.0f;
+      float xh[NIT][16], gh[NIT][16];
+#pragma unroll
+      for (int it = 0; it < NIT; ++it) {
+        float ux[16], ug[16];
+        unpack16_biased(cx[it], ux);
+        unpack16_biased(cgc[it], ug);
+        const float kx = sx[it] * rs, cx0 = __builtin_fmaf(-128.0f, kx, mrs);
+        const float g128 = -128.0f * sgv[it];
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          xh[it][e] = __builtin_fmaf(ux[e], kx, cx0);
+          const float gv = __builtin_fmaf(ug[e], sgv[it], g128);
+          gh[it][e] = gv * gm[it][e];
+          m1 += gh[it][e];
+          m2 = __builtin_fmaf(gh[it][e], xh[it][e], m2);
+          cgs[it][e] = __builtin_fmaf(gv, xh[it][e], cgs[it][e]);
+          cbs[it][e] += gv;
+        }
+      }
+      const float q1 = wave_group_sum<63>(m1) * inv_cols;
+      const float q2 = wave_group_sum<63>(m2) * inv_cols;
+      if (lane == 0) {
+        s_q[2 * (wave * RW + r)] = q1;
+        s_q[2 * (wave * RW + r) + 1] = q2;
+      }
+#pragma unroll
+      for (int it = 0; it < NIT; ++it) {
+        float m = 0.0f;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) m = fmaxf(m, fabsf(__builtin_fmaf(-xh[it][e], q2, gh[it][e] - q1)));
+        mloc[it] = fmaxf(mloc[it], m * rs);
+      }
+    }
+    constexpr int LM = B / 16 - 1;
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+      const float m = wave_group_max<LM>(mloc[it]);
+      const int c = lane + 64 * it;
+      if (ok[it] && (c & 1) == 0) s_amax[wave * ngran + (c >> 1)] = m;
+    }
+    __syncthreads();
+
+    // ---- pass B
+    float inv[NIT];
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+      const int c = lane + 64 * it;
+      float mm = 0.0f, scale;
+      if (ok[it]) {
+#pragma unroll
+        for (int w = 0; w < NW; ++w) mm = fmaxf(mm, s_amax[w * ngran + (c >> 1)]);
+      }
+      block_scale(mm, scale, inv[it]);
+      if (ok[it] && wave == 0 && ((16 * c) % B) == 0) SdX[(int64_t)bi * lc + (16 * c) / B] = scale;
+    }
+    load_row(X, r0, nx);
+    load_row(G, r0, ng);
+#pragma unroll 1
+    for (int r = 0; r < RW; ++r) {
+      uint4 cx[NIT], cgc[NIT];
+#pragma unroll
+      for (int it = 0; it < NIT; ++it) { cx[it] = nx[it]; cgc[it] = ng[it]; }
+      if (r + 1 < RW) {
+        load_row(X, r0 + r + 1, nx);
+        load_row(G, r0 + r + 1, ng);
+      }
+      const float mu = mean_in[r0 + r], rs = rstd_in[r0 + r];
+      const float mrs = -mu * rs;
+      const float q1 = s_q[2 * (wave * RW + r)], q2 = s_q[2 * (wave * RW + r) + 1];
+#pragma unroll
+      for (int it = 0; it < NIT; ++it) {
+        if (!ok[it]) continue;
+        float ux[16], ug[16], y[16];
+        unpack16_biased(cx[it], ux);
+        unpack16_biased(cgc[it], ug);
+        const float kx = sx[it] * rs, cx0 = __builtin_fmaf(-128.0f, kx, mrs);
+        const float g128 = -128.0f * sgv[it];
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const float xhv = __builtin_fmaf(ux[e], kx, cx0);
+          const float ghv = __builtin_fmaf(ug[e], sgv[it], g128) * gm[it][e];
+          y[e] = __builtin_fmaf(-xhv, q2, ghv - q1) * rs;
+        }
+        *reinterpret_cast<uint4*>(dX + (int64_t)(r0 + r) * cols + 16 * (lane + 64 * it)) = quantize16(y, inv[it]);
+      }
+    }
+    __syncthreads();  // max-abs slots and row means are rewritten by the next row block
+  }
+
+  // fold the column sums over the waves: wave w adds into LDS row w % 4 in round w / 4
+#pragma unroll
+  for (int it = 0; it < NIT; ++it) {
+#pragma unroll
+    for (int round = 0; round < NW / 4; ++round) {
+      if ((wave >> 2) == round && ok[it]) {
+        float* row_g = s_col + (wave & 3) * 2 * cols + 16 * (lane + 64 * it);
+        float* row_b = row_g + cols;
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+          float4 a = make_float4(cgs[it][4 * d], cgs[it][4 * d + 1], cgs[it][4 * d + 2], cgs[it][4 * d + 3]);
+          float4 b = make_float4(cbs[it][4 * d], cbs[it][4 * d + 1], cbs[it][4 * d + 2], cbs[it][4 * d + 3]);
+          if (round > 0) {
+            const float4 pa = *reinterpret_cast<const float4*>(row_g + 4 * d);
+            const float4 pb = *reinterpret_cast<const float4*>(row_b + 4 * d);
+            a = make_float4(pa.x + a.x, pa.y + a.y, pa.z + a.z, pa.w + a.w);
+            b = make_float4(pb.x + b.x, pb.y + b.y, pb.z + b.z, pb.w + b.w);
+          }
+          *reinterpret_cast<float4*>(row_g + 4 * d) = a;
+          *reinterpret_cast<float4*>(row_b + 4 * d) = b;
+        }
+      }
+      __syncthreads();
+    }
+  }
+  {  // the four folded rows, added in a fixed order -> one row of the workspace
+    float* dst = partials + (int64_t)blockIdx.x * 2 * cols;
+    for (int i = threadIdx.x; i < 2 * cols / 4; i += 64 * NW) {
+      const float4 a = *reinterpret_cast<const float4*>(s_col + 4 * i);
+      const float4 b = *reinterpret_cast<const float4*>(s_col + 2 * cols + 4 * i);
+      const float4 c = *reinterpret_cast<const float4*>(s_col + 4 * cols + 4 * i);
+      const float4 d = *reinterpret_cast<const float4*>(s_col + 6 * cols + 4 * i);
+      *reinterpret_cast<float4*>(dst + 4 * i) =
+          make_float4((a.x + b.x) + (c.x + d.x), (a.y + b.y) + (c.y + d.y), (a.z + b.z) + (c.z + d.z), (a.w + b.w) + (c.w + d.w));
+    }
+  }
+}
+
+// LayerNorm backward for rows wider than 2048 columns (a lane owns up to four chunk columns, too many for
+// running column sums in registers).  Sixteen waves per workgroup, RW = B/16 rows per wave.  Sweep 1: per row
 // m1 = mean_C(ghat), m2 = mean_C(ghat xhat), and per column the sums of g*xhat and g over the wave's rows;
 // the sixteen waves fold those column sums into four LDS rows in a fixed order (wave w adds into row w % 4
 // in round w / 4), which go to the workspace as four partial rows per workgroup.  Sweep 2:
 // dx = rstd (ghat - m1 - xhat m2) and its block max-abs; then quantize and store.
 template <int B, int NIT>
-__global__ void __launch_bounds__(1024) layernorm_bwd_kernel(const int8_t* __restrict__ G, const float* __restrict__ SG,
+__global__ void __launch_bounds__(1024) layernorm_bwd_wide_kernel(const int8_t* __restrict__ G, const float* __restrict__ SG,
                                                               const int8_t* __restrict__ X, const float* __restrict__ SX,
                                                               const float* __restrict__ gamma,
                                                               const float* __restrict__ mean_in,
@@ -601,7 +795,8 @@ static void launch_ln_fwd(dim3 grid, size_t lds, hipStream_t st, Args... args) {
 }
 template <int B, int NIT, typename... Args>
 static void launch_ln_bwd(dim3 grid, size_t lds, hipStream_t st, Args... args) {
-  hipLaunchKernelGGL((layernorm_bwd_kernel<B, NIT>), grid, dim3(1024), lds, st, args...);
+  if constexpr (NIT <= 2) hipLaunchKernelGGL((layernorm_bwd_kernel<B, NIT>), grid, dim3(512), lds, st, args...);
+  else hipLaunchKernelGGL((layernorm_bwd_wide_kernel<B, NIT>), grid, dim3(1024), lds, st, args...);
 }
 
 #define JF_LN_DISPATCH(FN, block, nit, ...)                                   \
@@ -677,10 +872,12 @@ extern "C" int32_t jf_layernorm_q_bwd(const int8_t* dY, const float* SdY, const 
   if (!aligned16(ws)) return JF_ERR_ALIGN;
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   float* partials = static_cast<float*>(ws);
-  const int nparts = (int)(N / block) * 4;
-  const dim3 grid((unsigned)(N / block));
+  const int nparts = (int)ln_bwd_partial_rows(N, C, block);
+  const dim3 grid((unsigned)(C > 2048 ? N / block : nparts));
   const int nit = (int)((C + 1023) / 1024);
-  const size_t lds = (16 * (size_t)(C / 32) + 4 * 2 * (size_t)C) * sizeof(float);  // max-abs slots + four column-sum rows
+  // max-abs slots per wave, (row means,) four column-sum rows
+  const size_t lds = C > 2048 ? (16 * (size_t)(C / 32) + 4 * 2 * (size_t)C) * sizeof(float)
+                              : (8 * (size_t)(C / 32) + 2 * (size_t)block + 4 * 2 * (size_t)C) * sizeof(float);
   JF_LN_DISPATCH(launch_ln_bwd, block, nit, grid, lds, st, dY, SdY, X, SX, gamma, mean, rstd, (int)N, (int)C, dX, SdX, partials);
   rc = launch_status();
   if (rc != JF_OK) return rc;

@@ -30,7 +30,7 @@ def test_error_strings_and_workspace():
     assert lib.jf_error_string(0) == b"JF_OK"
     for code in range(1, 8):
         assert lib.jf_error_string(code).startswith(b"JF_ERR_")
-    assert binding.jf_workspace_bytes(binding.JF_OP_LAYERNORM_BWD, 4096, 768, 0, 32) == 128 * 4 * 2 * 768 * 4
+    assert binding.jf_workspace_bytes(binding.JF_OP_LAYERNORM_BWD, 4096, 768, 0, 32) == 128 * 2 * 768 * 4
     assert binding.jf_workspace_bytes(binding.JF_OP_LINEAR_FWD, 4096, 768, 3072, 32) == 0
     assert binding.jf_workspace_bytes(binding.JF_OP_LAYERNORM_BWD, 4096, 768, 0, 48) == 0
 

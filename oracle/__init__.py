@@ -217,3 +217,44 @@ def layernorm_q_bwd(dY, SdY, X, SX, gamma, mean, rstd, block=32):
                                           _I64(C), _I32(block), _p(dX), _p(SdX), _p(dg), _p(db), _p(f)),
            "layernorm_q_bwd")
     return dX, SdX, dg, db, f
+
+
+def add_q(X1, S1, X2, S2, block=32):
+    """App. A (Add, with the row partials of the LayerNorm paragraph) + Alg. 2.
+
+    Returns (codes, scales, row_mean (N, C/B), row_sumsq (N, C/B), float64 sum)."""
+    X1, S1, X2, S2 = _i8(X1), _f32(S1), _i8(X2), _f32(S2)
+    N, C = X1.shape
+    assert X2.shape == (N, C)
+    Y = np.empty((N, C), np.int8)
+    SY = np.empty((N // block, C // block), np.float32)
+    rm = np.empty((N, C // block), np.float32)
+    rq = np.empty((N, C // block), np.float32)
+    f = np.empty((N, C), np.float64)
+    _check(_load().oracle_add_q(_p(X1), _p(S1), _p(X2), _p(S2), _I64(N), _I64(C), _I32(block), _p(Y), _p(SY), _p(rm),
+                                _p(rq), _p(f)), "add_q")
+    return Y, SY, rm, rq, f
+
+
+def row_stats_from_partials(row_mean, row_sumsq, C, eps=1e-5, block=32):
+    """App. A (LayerNorm paragraph): per-row mean and rstd from ADD's per-block row partials."""
+    row_mean, row_sumsq = _f32(row_mean), _f32(row_sumsq)
+    N = row_mean.shape[0]
+    assert row_mean.shape == row_sumsq.shape == (N, C // block)
+    mean = np.empty((N,), np.float32)
+    rstd = np.empty((N,), np.float32)
+    _check(_load().oracle_row_stats_from_partials(_p(row_mean), _p(row_sumsq), _I64(N), _I64(C), _I32(block),
+                                                  ctypes.c_float(eps), _p(mean), _p(rstd)), "row_stats_from_partials")
+    return mean, rstd
+
+
+def layernorm_q_stats(X, SX, gamma, beta, mean, rstd, block=32):
+    """App. A: LayerNorm from given row statistics + Alg. 2.  Returns (codes, scales, float64 pre-quantization values)."""
+    X, SX, gamma, beta, mean, rstd = _i8(X), _f32(SX), _f32(gamma), _f32(beta), _f32(mean), _f32(rstd)
+    N, C = X.shape
+    Y = np.empty((N, C), np.int8)
+    SY = np.empty((N // block, C // block), np.float32)
+    f = np.empty((N, C), np.float64)
+    _check(_load().oracle_layernorm_q_stats(_p(X), _p(SX), _p(gamma), _p(beta), _p(mean), _p(rstd), _I64(N), _I64(C),
+                                            _I32(block), _p(Y), _p(SY), _p(f)), "layernorm_q_stats")
+    return Y, SY, f

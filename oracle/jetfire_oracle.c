@@ -427,3 +427,85 @@ int oracle_layernorm_q_bwd(const int8_t* dY, const float* SdY, const int8_t* X, 
   free(db);
   return rc;
 }
+
+/* ------------------------------------------------------------------ */
+/* App. A, Add: y = x1 + x2 on the dequantized operands (the residual
+ * connection forward, and dx = df(y) + dy backward), then Alg. 2's quantize
+ * step.  The modified ADD of App. A (LayerNorm paragraph) also stores, for
+ * every row i and every block column j, the mean and the sum of squares of the
+ * FP32 sum over the B columns of that block: row_mean, row_sumsq are N x C/B
+ * FP32 matrices (both nullable).  y_f (nullable) receives the double sum. */
+int oracle_add_q(const int8_t* X1, const float* S1, const int8_t* X2, const float* S2, int64_t N, int64_t C, int block,
+                 int8_t* Y, float* SY, float* row_mean, float* row_sumsq, double* y_f) {
+  if (bad_shape(N, C, block)) return ORACLE_ERR_SHAPE;
+  double* a = (double*)malloc(sizeof(double) * N * C);
+  double* b = (double*)malloc(sizeof(double) * N * C);
+  if (!a || !b) {
+    free(a);
+    free(b);
+    return 3;
+  }
+  oracle_dequantize(X1, S1, N, C, block, a);
+  oracle_dequantize(X2, S2, N, C, block, b);
+  for (int64_t e = 0; e < N * C; ++e) a[e] += b[e];
+  const int64_t lc = C / block;
+  if (row_mean || row_sumsq) {
+    for (int64_t i = 0; i < N; ++i)
+      for (int64_t j = 0; j < lc; ++j) {
+        double s = 0.0, q = 0.0;
+        for (int c = 0; c < block; ++c) {
+          /* statistics of the FP32 values that Alg. 2 hands to the quantizer */
+          double v = (double)(float)a[i * C + j * block + c];
+          s += v;
+          q += v * v;
+        }
+        if (row_mean) row_mean[i * lc + j] = (float)(s / (double)block);
+        if (row_sumsq) row_sumsq[i * lc + j] = (float)q;
+      }
+  }
+  if (y_f) memcpy(y_f, a, sizeof(double) * N * C);
+  int rc = quantize_from_double(a, N, C, block, Y, SY);
+  free(a);
+  free(b);
+  return rc;
+}
+
+/* App. A (LayerNorm paragraph): row statistics from ADD's partials.  With L_C = C/B block columns,
+ *   mean_i = (1/L_C) sum_j row_mean[i][j],   E[x^2]_i = (1/C) sum_j row_sumsq[i][j],
+ *   var_i = E[x^2]_i - mean_i^2 (biased, clamped at 0),   rstd_i = 1/sqrt(var_i + eps). */
+int oracle_row_stats_from_partials(const float* row_mean, const float* row_sumsq, int64_t N, int64_t C, int block,
+                                   float eps, float* mean, float* rstd) {
+  if (bad_shape(N, C, block)) return ORACLE_ERR_SHAPE;
+  const int64_t lc = C / block;
+  for (int64_t i = 0; i < N; ++i) {
+    double s = 0.0, q = 0.0;
+    for (int64_t j = 0; j < lc; ++j) {
+      s += (double)row_mean[i * lc + j];
+      q += (double)row_sumsq[i * lc + j];
+    }
+    double mu = s / (double)lc;
+    double var = q / (double)C - mu * mu;
+    if (var < 0.0) var = 0.0;
+    mean[i] = (float)mu;
+    rstd[i] = (float)(1.0 / sqrt(var + (double)eps));
+  }
+  return ORACLE_OK;
+}
+
+/* App. A: LayerNorm that "directly accesses" given row statistics (FP32 mean, rstd):
+ * y = (x - mean) * rstd * gamma + beta on the dequantized input, then Alg. 2's quantize step. */
+int oracle_layernorm_q_stats(const int8_t* X, const float* SX, const float* gamma, const float* beta, const float* mean,
+                             const float* rstd, int64_t N, int64_t C, int block, int8_t* Y, float* SY, double* y_f) {
+  if (bad_shape(N, C, block)) return ORACLE_ERR_SHAPE;
+  double* y = (double*)malloc(sizeof(double) * N * C);
+  if (!y) return 3;
+  oracle_dequantize(X, SX, N, C, block, y);
+#pragma omp parallel for schedule(static)
+  for (int64_t i = 0; i < N; ++i)
+    for (int64_t j = 0; j < C; ++j)
+      y[i * C + j] = (y[i * C + j] - (double)mean[i]) * (double)rstd[i] * (double)gamma[j] + (double)beta[j];
+  if (y_f) memcpy(y_f, y, sizeof(double) * N * C);
+  int rc = quantize_from_double(y, N, C, block, Y, SY);
+  free(y);
+  return rc;
+}

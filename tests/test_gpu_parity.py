@@ -288,7 +288,8 @@ def test_gelu_fwd_bwd(block, N, C):
 
 
 # --------------------------------------------------------------------------- LayerNorm
-@pytest.mark.parametrize("block,N,C", [(32, 96, 352), (32, 64, 1280), (64, 128, 192), (128, 256, 384), (32, 4096, 768)])
+@pytest.mark.parametrize("block,N,C", [(32, 96, 352), (32, 64, 1280), (64, 128, 192), (128, 256, 384), (32, 4096, 768),
+                                       (32, 64, 4096), (64, 128, 2304), (32, 19200, 96)])
 def test_layernorm_fwd_bwd(block, N, C):
     say(f"layernorm block={block} {N}x{C}")
     x, gamma, beta, gr = workloads.layernorm_case(6000 + block + N, N, C)

@@ -373,3 +373,88 @@ def test_layernorm_backward_finite_difference():
         e[i, j] = h
         fd = ((ln(xd + e) - ln(xd - e)) * gd).sum() / (2 * h)
         assert abs(dx[i, j] - fd) < 2e-6 * np.abs(dx).max()
+
+
+# --------------------------------------------------------------------------- Add with row partials (App. A)
+def _two_tensors(seed, N, C, block):
+    g = workloads.rng(seed)
+    x1 = workloads.gaussian(g, N, C, 1.0)
+    workloads.with_outlier_columns(g, x1, 0.01, 20.0)
+    x2 = workloads.gaussian(g, N, C, 0.3, mean=0.1)
+    return oracle.quantize_block(x1, block), oracle.quantize_block(x2, block)
+
+
+@pytest.mark.parametrize("block", [32, 64])
+def test_add_equals_numpy_sum_of_dequantized_and_commutes(block):
+    N, C = 2 * block, 3 * block
+    (X1, S1), (X2, S2) = _two_tensors(700 + block, N, C, block)
+    Y, SY, rm, rq, f = oracle.add_q(X1, S1, X2, S2, block)
+    want = oracle.dequantize(X1, S1, block) + oracle.dequantize(X2, S2, block)       # library float64 addition
+    np.testing.assert_array_equal(f, want)
+    # the output is Eq. 1 applied to the FP32 sum: same pins as the quantizer
+    q, s = oracle.quantize_block(want.astype(np.float32), block)
+    np.testing.assert_array_equal(Y, q)
+    np.testing.assert_array_equal(SY, s)
+    Y2, SY2, rm2, rq2, _ = oracle.add_q(X2, S2, X1, S1, block)
+    np.testing.assert_array_equal(Y, Y2)
+    np.testing.assert_array_equal(SY, SY2)
+    np.testing.assert_array_equal(rm, rm2)
+    np.testing.assert_array_equal(rq, rq2)
+
+
+def test_add_of_zero_tensor_requantizes_to_the_same_codes():
+    block, N, C = 32, 64, 96
+    (X1, S1), _ = _two_tensors(711, N, C, block)
+    Z, SZ = np.zeros((N, C), np.int8), np.zeros((N // block, C // block), np.float32)
+    Y, SY, _, _, _ = oracle.add_q(X1, S1, Z, SZ, block)
+    np.testing.assert_array_equal(Y, X1)
+    np.testing.assert_allclose(SY, S1, rtol=2e-7)
+
+
+def test_add_row_partials_against_numpy_and_row_statistics():
+    """Row partials: mean and sum of squares over each block's columns; combining them gives the row mean and
+    the biased row variance of the whole row (checked against numpy on the full rows)."""
+    block, N, C = 32, 64, 160
+    (X1, S1), (X2, S2) = _two_tensors(720, N, C, block)
+    Y, SY, rm, rq, f = oracle.add_q(X1, S1, X2, S2, block)
+    y32 = f.astype(np.float32).astype(np.float64)
+    blocks = y32.reshape(N, C // block, block)
+    np.testing.assert_allclose(rm, blocks.mean(axis=2), rtol=1e-6, atol=1e-7)
+    np.testing.assert_allclose(rq, (blocks ** 2).sum(axis=2), rtol=1e-6)
+    eps = 1e-5
+    mean, rstd = oracle.row_stats_from_partials(rm, rq, C, eps, block)
+    np.testing.assert_allclose(mean, y32.mean(axis=1), rtol=0, atol=2e-6)
+    np.testing.assert_allclose(rstd, 1.0 / np.sqrt(y32.var(axis=1) + eps), rtol=1e-5)
+    # a constant row has variance 0 whatever its mean
+    rm_c = np.full((block, C // block), 7.0, np.float32)
+    rq_c = np.full((block, C // block), 49.0 * block, np.float32)
+    mean_c, rstd_c = oracle.row_stats_from_partials(rm_c, rq_c, C, eps, block)
+    assert mean_c[0] == 7.0 and abs(rstd_c[0] - 1.0 / math.sqrt(eps)) < 1e-2
+
+
+def test_layernorm_from_statistics_matches_torch_and_the_self_statistics_operator():
+    block, N, C = 32, 64, 96
+    x, gamma, beta, _ = workloads.layernorm_case(730, N, C)
+    X, SX = oracle.quantize_block(x, block)
+    xd = oracle.dequantize(X, SX, block)
+    eps = 1e-5
+    # statistics of the dequantized tensor itself, via ADD with a zero tensor: then the operator must agree with
+    # the LayerNorm that computes its own statistics, and with torch's float64 layer_norm
+    Z, SZ = np.zeros((N, C), np.int8), np.zeros((N // block, C // block), np.float32)
+    _, _, rm, rq, _ = oracle.add_q(X, SX, Z, SZ, block)
+    mean, rstd = oracle.row_stats_from_partials(rm, rq, C, eps, block)
+    Y, SY, f = oracle.layernorm_q_stats(X, SX, gamma, beta, mean, rstd, block)
+    Y0, SY0, mean0, rstd0, f0 = oracle.layernorm_q(X, SX, gamma, beta, eps, block)
+    np.testing.assert_allclose(mean, mean0, rtol=0, atol=1e-6 * np.abs(xd).max())
+    np.testing.assert_allclose(rstd, rstd0, rtol=1e-5)
+    want = torch.nn.functional.layer_norm(torch.from_numpy(xd), (C,), torch.from_numpy(gamma.astype(np.float64)),
+                                          torch.from_numpy(beta.astype(np.float64)), eps).numpy()
+    np.testing.assert_allclose(f, want, rtol=0, atol=2e-5 * np.abs(want).max())
+    assert np.abs(Y.astype(int) - Y0.astype(int)).max() <= 1
+    np.testing.assert_allclose(SY, SY0, rtol=1e-5)
+    # statistics that differ from the tensor's own are used as given: y = (x - m) r gamma + beta
+    m2 = (mean + 0.25).astype(np.float32)
+    r2 = (rstd * 0.5).astype(np.float32)
+    _, _, f2 = oracle.layernorm_q_stats(X, SX, gamma, beta, m2, r2, block)
+    np.testing.assert_allclose(f2, (xd - m2[:, None].astype(np.float64)) * r2[:, None].astype(np.float64) * gamma + beta,
+                               rtol=1e-12, atol=1e-12)

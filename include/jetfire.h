@@ -149,6 +149,29 @@ int32_t jf_layernorm_q(const int8_t* X, const float* SX, const float* gamma, con
                        int64_t C, int32_t block, int8_t* Y, float* SY, float* mean, float* rstd, void* stream);
 
 /*
+ * INT8 LayerNorm that takes its row statistics from the partials of the
+ * preceding Add (App. A, LayerNorm paragraph) instead of a pass over X:
+ *   mean_i = (1/L_C) sum_j row_mean[i][j],  E[x^2]_i = (1/C) sum_j row_sumsq[i][j],
+ *   var_i = max(E[x^2]_i - mean_i^2, 0),  rstd_i = 1/sqrt(var_i + eps),
+ * then y = (x - mean) * rstd * gamma + beta on the dequantized X as above.
+ * row_mean, row_sumsq: FP32 N x (C/block), row-major, as written by jf_add_q.
+ */
+int32_t jf_layernorm_q_partials(const int8_t* X, const float* SX, const float* row_mean, const float* row_sumsq,
+                                const float* gamma, const float* beta, float eps, int64_t N, int64_t C, int32_t block,
+                                int8_t* Y, float* SY, float* mean, float* rstd, void* stream);
+
+/*
+ * INT8 Add (App. A): Y = Q(X1 + X2) on the dequantized operands, the residual
+ * connection forward and dx = df(y) + dy backward.  X1, X2: N x C codes with
+ * grids S1, S2; Y, SY out.  row_mean / row_sumsq (both NULL or both non-NULL,
+ * FP32 N x (C/block)) receive, for every row and block column, the mean and
+ * the sum of squares of the FP32 sum over the block's columns -- the row
+ * partials that App. A attaches to this operator for the LayerNorm after it.
+ */
+int32_t jf_add_q(const int8_t* X1, const float* S1, const int8_t* X2, const float* S2, int64_t N, int64_t C,
+                 int32_t block, int8_t* Y, float* SY, float* row_mean, float* row_sumsq, void* stream);
+
+/*
  * INT8 LayerNorm backward (standard LayerNorm gradient on dequantized
  * operands).  xhat = (x - mean) rstd, ghat = dY * gamma:
  *   dX = rstd (ghat - mean_C(ghat) - xhat mean_C(ghat xhat)),

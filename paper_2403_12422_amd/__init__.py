@@ -7,12 +7,14 @@ library or without a GPU raises.
 """
 from .binding import (  # noqa: F401
     JetfireError,
+    jf_add_q,
     jf_debug_linear_partials,
     jf_debug_set_gemm_shape,
     jf_gelu_q,
     jf_gelu_q_bwd,
     jf_layernorm_q,
     jf_layernorm_q_bwd,
+    jf_layernorm_q_partials,
     jf_linear_dgrad,
     jf_linear_fwd,
     jf_linear_wgrad,

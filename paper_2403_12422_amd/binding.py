@@ -24,6 +24,8 @@ _SIGNATURES = {
     "jf_gelu_q": (_I32, [_P, _P, _I64, _I64, _I32, _P, _P, _P]),
     "jf_gelu_q_bwd": (_I32, [_P, _P, _P, _P, _I64, _I64, _I32, _P, _P, _P]),
     "jf_layernorm_q": (_I32, [_P, _P, _P, _P, _F32, _I64, _I64, _I32, _P, _P, _P, _P, _P]),
+    "jf_layernorm_q_partials": (_I32, [_P, _P, _P, _P, _P, _P, _F32, _I64, _I64, _I32, _P, _P, _P, _P, _P]),
+    "jf_add_q": (_I32, [_P, _P, _P, _P, _I64, _I64, _I32, _P, _P, _P, _P, _P]),
     "jf_layernorm_q_bwd": (_I32, [_P, _P, _P, _P, _P, _P, _P, _I64, _I64, _I32, _P, _P, _P, _P, _P, _SZ, _P]),
     "jf_debug_linear_partials": (_I32, [_I32, _P, _P, _I64, _I64, _I64, _I32, _I64, _P, _P]),
     "jf_debug_set_gemm_shape": (_I32, [_I32]),
@@ -189,6 +191,47 @@ def jf_layernorm_q(X, SX, gamma, beta, eps=1e-5, block=32, out=None):
     _check(load_library().jf_layernorm_q(_ptr(X), _ptr(SX), _ptr(gamma), _ptr(beta), eps, N, C, block, _ptr(Y),
                                          _ptr(SY), _ptr(mean), _ptr(rstd), _stream()))
     return Y, SY, mean, rstd
+
+
+def jf_layernorm_q_partials(X, SX, row_mean, row_sumsq, gamma, beta, eps=1e-5, block=32, out=None):
+    """LayerNorm whose row statistics come from the row partials written by jf_add_q."""
+    _dev(X, torch.int8, 2), _dev(SX, torch.float32, 2), _dev(gamma, torch.float32, 1), _dev(beta, torch.float32, 1)
+    _dev(row_mean, torch.float32, 2), _dev(row_sumsq, torch.float32, 2)
+    N, C = X.shape
+    if tuple(row_mean.shape) != (N, C // block) or tuple(row_sumsq.shape) != (N, C // block):
+        raise JetfireError(2, "row partials must be (N, C / block)")
+    if out is not None:
+        Y, SY, mean, rstd = out
+    else:
+        Y = torch.empty_like(X)
+        SY = torch.empty_like(SX)
+        mean = torch.empty((N,), dtype=torch.float32, device=X.device)
+        rstd = torch.empty((N,), dtype=torch.float32, device=X.device)
+    _check(load_library().jf_layernorm_q_partials(_ptr(X), _ptr(SX), _ptr(row_mean), _ptr(row_sumsq), _ptr(gamma),
+                                                  _ptr(beta), eps, N, C, block, _ptr(Y), _ptr(SY), _ptr(mean),
+                                                  _ptr(rstd), _stream()))
+    return Y, SY, mean, rstd
+
+
+def jf_add_q(X1, S1, X2, S2, block=32, want_partials=False, out=None):
+    """Y = Q(X1 + X2); with want_partials also the (N, C/block) row partials (mean, sum of squares) of the sum."""
+    _dev(X1, torch.int8, 2), _dev(S1, torch.float32, 2), _dev(X2, torch.int8, 2), _dev(S2, torch.float32, 2)
+    N, C = X1.shape
+    if X2.shape != X1.shape:
+        raise JetfireError(2, "X1 and X2 shapes differ")
+    rm = rq = None
+    if out is not None:
+        Y, SY = out[0], out[1]
+        if want_partials:
+            rm, rq = out[2], out[3]
+    else:
+        Y, SY = torch.empty_like(X1), torch.empty_like(S1)
+        if want_partials:
+            rm = torch.empty((N, C // block), dtype=torch.float32, device=X1.device)
+            rq = torch.empty((N, C // block), dtype=torch.float32, device=X1.device)
+    _check(load_library().jf_add_q(_ptr(X1), _ptr(S1), _ptr(X2), _ptr(S2), N, C, block, _ptr(Y), _ptr(SY), _ptr(rm),
+                                   _ptr(rq), _stream()))
+    return (Y, SY, rm, rq) if want_partials else (Y, SY)
 
 
 def jf_layernorm_q_bwd(dY, SdY, X, SX, gamma, mean, rstd, block=32, workspace=None, out=None):

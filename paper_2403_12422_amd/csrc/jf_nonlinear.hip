@@ -189,6 +189,70 @@ __global__ void __launch_bounds__(256) gelu_kernel(const int8_t* __restrict__ X,
 }
 
 // ------------------------------------------------------------------------------------------------
+// Add (App. A): y = x1 + x2 on the dequantized operands, re-quantized per block (Alg. 2), and optionally
+// the row partials that App. A's LayerNorm paragraph attaches to this operator: for every row and block
+// column, the mean and the sum of squares of y over the block's B columns.  Same tiling as GELU.
+template <int B>
+__global__ void __launch_bounds__(256) add_kernel(const int8_t* __restrict__ X1, const float* __restrict__ S1,
+                                                   const int8_t* __restrict__ X2, const float* __restrict__ S2, int rows,
+                                                   int cols, int8_t* __restrict__ Y, float* __restrict__ SY,
+                                                   float* __restrict__ row_mean, float* __restrict__ row_sumsq) {
+  constexpr int P = B / 32;
+  constexpr int CH = B >= 128 ? 7 : (B == 64 ? 3 : 1);  // chunk lanes of one block column
+  __shared__ float s_amax[4][4];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int ch = lane & 7, rsub = lane >> 3;
+  const int col = blockIdx.x * 128 + 16 * ch;
+  const int r0 = blockIdx.y * B + wave * (B / 4);
+  const bool col_ok = col < cols;
+  const int lc = cols / B, bi = blockIdx.y;
+
+  float y[P][16];
+  float m = 0.0f;
+  if (col_ok) {
+    const float s1 = S1[(int64_t)bi * lc + col / B], s2 = S2[(int64_t)bi * lc + col / B];
+    const float k = -128.0f * (s1 + s2);  // the unpacked codes carry +128
+#pragma unroll
+    for (int p = 0; p < P; ++p) {
+      const int row = r0 + 8 * p + rsub;
+      float u1[16], u2[16];
+      unpack16_biased(*reinterpret_cast<const uint4*>(X1 + (int64_t)row * cols + col), u1);
+      unpack16_biased(*reinterpret_cast<const uint4*>(X2 + (int64_t)row * cols + col), u2);
+      float ps = 0.0f, pq = 0.0f;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        y[p][e] = __builtin_fmaf(u1[e], s1, __builtin_fmaf(u2[e], s2, k));
+        ps += y[p][e];
+        pq = __builtin_fmaf(y[p][e], y[p][e], pq);
+      }
+#pragma unroll
+      for (int e = 0; e < 16; e += 4) m = amax4(m, y[p][e], y[p][e + 1], y[p][e + 2], y[p][e + 3]);
+      if (row_mean != nullptr) {  // uniform over the grid
+        ps = wave_group_sum<CH>(ps);
+        pq = wave_group_sum<CH>(pq);
+        if ((ch & CH) == 0) {
+          row_mean[(int64_t)row * lc + col / B] = ps * (1.0f / (float)B);
+          row_sumsq[(int64_t)row * lc + col / B] = pq;
+        }
+      }
+    }
+  }
+  m = strip_block_max<B>(m);
+  if ((lane & 57) == 0) s_amax[wave][ch >> 1] = m;
+  __syncthreads();
+  m = fmaxf(fmaxf(s_amax[0][ch >> 1], s_amax[1][ch >> 1]), fmaxf(s_amax[2][ch >> 1], s_amax[3][ch >> 1]));
+  float scale, inv;
+  block_scale(m, scale, inv);
+  if (!col_ok) return;
+  if (wave == 0 && rsub == 0 && (col % B) == 0) SY[(int64_t)bi * lc + col / B] = scale;
+#pragma unroll
+  for (int p = 0; p < P; ++p) {
+    const int row = r0 + 8 * p + rsub;
+    *reinterpret_cast<uint4*>(Y + (int64_t)row * cols + col) = quantize16(y[p], inv);
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
 // LayerNorm.  One workgroup of four waves owns B rows and all C columns; wave w owns rows
 // [w*B/4, (w+1)*B/4).  Lane l of a wave owns the 16-byte chunks l, l+64, ... of each of its rows, so a
 // row is read as contiguous 1 KB runs and per-column quantities (gamma, beta, column sums) stay in
@@ -221,7 +285,9 @@ __global__ void __launch_bounds__(1024) layernorm_fwd_kernel(const int8_t* __res
                                                               const float* __restrict__ gamma,
                                                               const float* __restrict__ beta, float eps, int rows,
                                                               int cols, int8_t* __restrict__ Y, float* __restrict__ SY,
-                                                              float* __restrict__ mean_out, float* __restrict__ rstd_out) {
+                                                              float* __restrict__ mean_out, float* __restrict__ rstd_out,
+                                                              const float* __restrict__ row_mean,
+                                                              const float* __restrict__ row_sumsq) {
   constexpr int NW = 16, RW = B / NW;
   constexpr bool KEEP = RW * NIT <= 8;
   extern __shared__ float s_dyn[];  // [NW][C/32] per-wave block max-abs
@@ -257,14 +323,24 @@ __global__ void __launch_bounds__(1024) layernorm_fwd_kernel(const int8_t* __res
 #pragma unroll
   for (int r = 0; r < RW; ++r) {
     double ds = 0.0, dq = 0.0;
+    if (row_mean != nullptr) {
+      // statistics handed over by the preceding Add (App. A): per block column the mean and the sum of
+      // squares over its B columns; the row sum is B times the sum of the block means
+      for (int j = lane; j < lc; j += 64) {
+        ds += (double)row_mean[(int64_t)(r0 + r) * lc + j];
+        dq += (double)row_sumsq[(int64_t)(r0 + r) * lc + j];
+      }
+      ds *= (double)B;
+    } else {
 #pragma unroll
-    for (int it = 0; it < NIT; ++it) {
-      if (ok[it]) {
-        int s1, s2;
-        chunk_moments(chunk(r, it), s1, s2);
-        const double sd = (double)sx[it];
-        ds += sd * (double)s1;
-        dq += sd * sd * (double)s2;
+      for (int it = 0; it < NIT; ++it) {
+        if (ok[it]) {
+          int s1, s2;
+          chunk_moments(chunk(r, it), s1, s2);
+          const double sd = (double)sx[it];
+          ds += sd * (double)s1;
+          dq += sd * sd * (double)s2;
+        }
       }
     }
     const double sum = wave_group_sum_f64<63>(ds);
@@ -838,9 +914,9 @@ extern "C" int32_t jf_gelu_q_bwd(const int8_t* dY, const float* SdY, const int8_
   return launch_status();
 }
 
-extern "C" int32_t jf_layernorm_q(const int8_t* X, const float* SX, const float* gamma, const float* beta, float eps,
-                                  int64_t N, int64_t C, int32_t block, int8_t* Y, float* SY, float* mean, float* rstd,
-                                  void* stream) {
+static int32_t layernorm_fwd(const int8_t* X, const float* SX, const float* row_mean, const float* row_sumsq,
+                             const float* gamma, const float* beta, float eps, int64_t N, int64_t C, int32_t block,
+                             int8_t* Y, float* SY, float* mean, float* rstd, void* stream) {
   using namespace jf;
   int32_t rc = check_eltwise(X, SX, Y, SY, N, C, block);
   if (rc != JF_OK) return rc;
@@ -851,7 +927,40 @@ extern "C" int32_t jf_layernorm_q(const int8_t* X, const float* SX, const float*
   const dim3 grid((unsigned)(N / block));
   const int nit = (int)((C + 1023) / 1024);
   const size_t lds = 16 * (size_t)(C / 32) * sizeof(float);
-  JF_LN_DISPATCH(launch_ln_fwd, block, nit, grid, lds, st, X, SX, gamma, beta, eps, (int)N, (int)C, Y, SY, mean, rstd);
+  JF_LN_DISPATCH(launch_ln_fwd, block, nit, grid, lds, st, X, SX, gamma, beta, eps, (int)N, (int)C, Y, SY, mean, rstd,
+                 row_mean, row_sumsq);
+  return launch_status();
+}
+
+extern "C" int32_t jf_layernorm_q(const int8_t* X, const float* SX, const float* gamma, const float* beta, float eps,
+                                  int64_t N, int64_t C, int32_t block, int8_t* Y, float* SY, float* mean, float* rstd,
+                                  void* stream) {
+  return layernorm_fwd(X, SX, nullptr, nullptr, gamma, beta, eps, N, C, block, Y, SY, mean, rstd, stream);
+}
+
+extern "C" int32_t jf_layernorm_q_partials(const int8_t* X, const float* SX, const float* row_mean,
+                                           const float* row_sumsq, const float* gamma, const float* beta, float eps,
+                                           int64_t N, int64_t C, int32_t block, int8_t* Y, float* SY, float* mean,
+                                           float* rstd, void* stream) {
+  if (!row_mean || !row_sumsq) return JF_ERR_NULL;
+  if (!jf::aligned4(row_mean) || !jf::aligned4(row_sumsq)) return JF_ERR_ALIGN;
+  return layernorm_fwd(X, SX, row_mean, row_sumsq, gamma, beta, eps, N, C, block, Y, SY, mean, rstd, stream);
+}
+
+extern "C" int32_t jf_add_q(const int8_t* X1, const float* S1, const int8_t* X2, const float* S2, int64_t N, int64_t C,
+                            int32_t block, int8_t* Y, float* SY, float* row_mean, float* row_sumsq, void* stream) {
+  using namespace jf;
+  int32_t rc = check_eltwise(X1, S1, Y, SY, N, C, block);
+  if (rc != JF_OK) return rc;
+  if (!X2 || !S2) return JF_ERR_NULL;
+  if ((row_mean == nullptr) != (row_sumsq == nullptr)) return JF_ERR_NULL;
+  if (!aligned16(X2) || !aligned4(S2) || (row_mean && (!aligned4(row_mean) || !aligned4(row_sumsq)))) return JF_ERR_ALIGN;
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  const dim3 grid((unsigned)((C + 127) / 128), (unsigned)(N / block));
+  const int rows = (int)N, cols = (int)C;
+  if (block == 32) hipLaunchKernelGGL((add_kernel<32>), grid, dim3(256), 0, st, X1, S1, X2, S2, rows, cols, Y, SY, row_mean, row_sumsq);
+  else if (block == 64) hipLaunchKernelGGL((add_kernel<64>), grid, dim3(256), 0, st, X1, S1, X2, S2, rows, cols, Y, SY, row_mean, row_sumsq);
+  else hipLaunchKernelGGL((add_kernel<128>), grid, dim3(256), 0, st, X1, S1, X2, S2, rows, cols, Y, SY, row_mean, row_sumsq);
   return launch_status();
 }
 

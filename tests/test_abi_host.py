@@ -68,6 +68,11 @@ def test_argument_validation_returns_codes_without_launching():
     assert lib.jf_gelu_q_bwd(None, FAKE, FAKE, FAKE, 64, 64, 32, FAKE, FAKE, None) == 1
     assert lib.jf_layernorm_q(FAKE, FAKE, None, FAKE, ctypes.c_float(1e-5), 64, 64, 32, FAKE, FAKE, FAKE, FAKE, None) == 1
     assert lib.jf_layernorm_q_bwd(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 64, 64, 32, FAKE, FAKE, FAKE, FAKE, FAKE, 16, None) == 5
+    assert lib.jf_add_q(FAKE, FAKE, None, FAKE, 64, 64, 32, FAKE, FAKE, None, None, None) == 1
+    assert lib.jf_add_q(FAKE, FAKE, FAKE, FAKE, 64, 64, 32, FAKE, FAKE, FAKE, None, None) == 1      # partials come together
+    assert lib.jf_add_q(FAKE, FAKE, FAKE, FAKE, 64, 80, 32, FAKE, FAKE, None, None, None) == 2
+    assert lib.jf_layernorm_q_partials(FAKE, FAKE, None, FAKE, FAKE, FAKE, ctypes.c_float(1e-5), 64, 64, 32, FAKE, FAKE, FAKE,
+                                       FAKE, None) == 1
     assert lib.jf_debug_linear_partials(0, FAKE, FAKE, 64, 64, 64, 32, 2, FAKE, None) == 2   # kb out of range
     assert lib.jf_debug_linear_partials(3, FAKE, FAKE, 64, 64, 64, 32, 0, FAKE, None) == 2
 

@@ -318,6 +318,39 @@ def test_layernorm_fwd_bwd(block, N, C):
     assert torch.equal(dgam, dgam2) and torch.equal(dbet, dbet2) and torch.equal(dX, dX2)
 
 
+# --------------------------------------------------------------------------- Add with row partials, LayerNorm from them
+@pytest.mark.parametrize("block,N,C", [(32, 96, 352), (64, 128, 192), (128, 256, 384), (32, 8192, 1280)])
+def test_add_and_layernorm_from_partials(block, N, C):
+    say(f"add + layernorm from partials block={block} {N}x{C}")
+    g = workloads.rng(7000 + block + N)
+    x1 = workloads.gaussian(g, N, C, 1.0)
+    workloads.with_outlier_columns(g, x1, 0.01, 20.0)
+    x2 = workloads.gaussian(g, N, C, 0.3, mean=0.1)
+    x1[:block, :block] = 0.0
+    x2[:block, :block] = 0.0                                    # an all-zero output block
+    (X1, S1), (X2, S2) = oracle.quantize_block(x1, block), oracle.quantize_block(x2, block)
+    gamma = (1.0 + 0.1 * g.standard_normal(C, dtype=np.float32)).astype(np.float32)
+    beta = (0.1 * g.standard_normal(C, dtype=np.float32)).astype(np.float32)
+    X1d, S1d, X2d, S2d, gd, bd = map(dev, (X1, S1, X2, S2, gamma, beta))
+    Y, SY, rm, rq = jf.jf_add_q(X1d, S1d, X2d, S2d, block, want_partials=True)
+    oY, oSY, orm, orq, of = oracle.add_q(X1, S1, X2, S2, block)
+    _check_eltwise("add", Y, SY, oY, oSY, of, block)
+    Yn, SYn = jf.jf_add_q(X1d, S1d, X2d, S2d, block)            # without partials: same codes
+    assert torch.equal(Y, Yn) and torch.equal(SY, SYn)
+    # partials are FP32 sums of B terms: tolerance relative to the sum of magnitudes
+    absum = np.abs(of).reshape(N, C // block, block).sum(axis=2)
+    assert np.all(np.abs(host(rm).astype(np.float64) - orm) <= 1e-5 * absum / block + 1e-30)
+    assert np.all(np.abs(host(rq).astype(np.float64) - orq) <= 1e-5 * orq + 1e-30)
+    # LayerNorm from the ORACLE's partials, so that both sides start from identical inputs
+    eps = 1e-5
+    Z, SZ, mean, rstd = jf.jf_layernorm_q_partials(dev(oY), dev(oSY), dev(orm), dev(orq), gd, bd, eps, block)
+    omean, orstd = oracle.row_stats_from_partials(orm, orq, C, eps, block)
+    oZ, oSZ, oz = oracle.layernorm_q_stats(oY, oSY, gamma, beta, omean, orstd, block)
+    np.testing.assert_allclose(host(mean), omean, rtol=0, atol=1e-5 * np.abs(of).max())
+    np.testing.assert_allclose(host(rstd), orstd, rtol=1e-5)
+    _check_eltwise("layernorm from partials", Z, SZ, oZ, oSZ, oz, block)
+
+
 # --------------------------------------------------------------------------- large-GEMM sweep (config 5)
 # Every shape of the sweep and every block size appear at least once; the full cross product would only
 # repeat the same code paths.  Each product is checked on sampled output blocks (each over the full K, FP32

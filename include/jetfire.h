@@ -94,6 +94,16 @@ int32_t jf_quantize_block(const void* x, int32_t x_dtype, int64_t rows, int64_t 
                           int8_t* q, int64_t ldq, float* s, int8_t* qT, int64_t ldqT, float* sT, void* stream);
 
 /*
+ * Dequantizer Q^-1 of Sec. 4, Eq. 1: out = code * scale, the hand-over from
+ * the INT8 data flow to a floating-point operator (Sec. 7.1 keeps multi-head
+ * attention in FP16).  q rows x cols codes (dense), s scale grid;
+ * out rows x cols with leading dimension ldo (elements), out_dtype 0 = FP32,
+ * 1 = FP16 (the FP32 product rounded to nearest even).
+ */
+int32_t jf_dequantize_block(const int8_t* q, const float* s, int64_t rows, int64_t cols, int32_t block, void* out,
+                            int32_t out_dtype, int64_t ldo, void* stream);
+
+/*
  * INT8 linear layer, forward product Y = X W^T (Sec. 4; Sec. 5 Eq. 2; Alg. 1).
  *   X  N x C codes, SX (N/B) x (C/B);  W  D x C codes, SW (D/B) x (C/B).
  *   Y  out N x D codes, SY out (N/B) x (D/B).

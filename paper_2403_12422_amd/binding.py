@@ -18,6 +18,7 @@ _SIGNATURES = {
     "jf_error_string": (ctypes.c_char_p, [_I32]),
     "jf_workspace_bytes": (_SZ, [_I32, _I64, _I64, _I64, _I32]),
     "jf_quantize_block": (_I32, [_P, _I32, _I64, _I64, _I64, _I32, _P, _I64, _P, _P, _I64, _P, _P]),
+    "jf_dequantize_block": (_I32, [_P, _P, _I64, _I64, _I32, _P, _I32, _I64, _P]),
     "jf_linear_fwd": (_I32, [_P, _P, _P, _P, _I64, _I64, _I64, _I32, _P, _P, _P, _P, _SZ, _P]),
     "jf_linear_dgrad": (_I32, [_P, _P, _P, _P, _I64, _I64, _I64, _I32, _P, _P, _P, _P, _SZ, _P]),
     "jf_linear_wgrad": (_I32, [_P, _P, _P, _P, _I64, _I64, _I64, _I32, _P, _P, _P, _P, _SZ, _P]),
@@ -115,6 +116,19 @@ def jf_quantize_block(x, block=32, transposed_copy=False, out=None):
     _check(lib.jf_quantize_block(_ptr(x), 0 if x.dtype == torch.float32 else 1, rows, cols, cols, block, _ptr(q), cols,
                                  _ptr(s), _ptr(qT), rows, _ptr(sT), _stream()))
     return (q, s, qT, sT) if transposed_copy else (q, s)
+
+
+def jf_dequantize_block(q, s, block=32, dtype=torch.float32, out=None):
+    """(codes, scales) -> float32 or float16 tensor of code * scale."""
+    _dev(q, torch.int8, 2), _dev(s, torch.float32, 2)
+    if dtype not in (torch.float32, torch.float16):
+        raise JetfireError(7, "output must be float32 or float16")
+    rows, cols = q.shape
+    if out is None:
+        out = torch.empty((rows, cols), dtype=dtype, device=q.device)
+    _check(load_library().jf_dequantize_block(_ptr(q), _ptr(s), rows, cols, block, _ptr(out),
+                                              0 if dtype == torch.float32 else 1, cols, _stream()))
+    return out
 
 
 def _linear(fn, a, sa, b, sb, N, C, D, block, out_shape, want_q, want_f32, out=None):

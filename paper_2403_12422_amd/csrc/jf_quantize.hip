@@ -121,7 +121,62 @@ static void dispatch_quantize(int block, const T* x, int64_t ldx, int rows, int 
   else launch_quantize<T, 128>(x, ldx, rows, cols, q, ldq, s, qT, ldqT, sT, st);
 }
 
+// Dequantizer Q^-1 of Eq. 1: out = code * scale as FP32 or FP16 (the hand-over to a floating-point operator
+// such as the FP16 attention core of Sec. 7.1).  A thread converts 16 consecutive codes of one row.
+template <typename T>
+__global__ void __launch_bounds__(256) dequantize_kernel(const int8_t* __restrict__ q, const float* __restrict__ s, int rows,
+                                                          int cols, int block, T* __restrict__ out, int64_t ldo) {
+  const int chunks = cols / 16;
+  const int64_t total = (int64_t)rows * chunks;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+    const int row = (int)(i / chunks), col = 16 * (int)(i % chunks);
+    const uint4 p = *reinterpret_cast<const uint4*>(q + (int64_t)row * cols + col);
+    const float sc = s[(int64_t)(row / block) * (cols / block) + col / block];
+    const uint32_t w[4] = {p.x, p.y, p.z, p.w};
+    float v[16];
+#pragma unroll
+    for (int d = 0; d < 4; ++d)
+#pragma unroll
+      for (int b = 0; b < 4; ++b) v[4 * d + b] = (float)(int8_t)(w[d] >> (8 * b)) * sc;
+    T* dst = out + (int64_t)row * ldo + col;
+    if constexpr (sizeof(T) == 4) {
+#pragma unroll
+      for (int d = 0; d < 4; ++d)
+        *reinterpret_cast<float4*>(dst + 4 * d) = make_float4(v[4 * d], v[4 * d + 1], v[4 * d + 2], v[4 * d + 3]);
+    } else {
+      typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+#pragma unroll
+      for (int d = 0; d < 2; ++d) {
+        h8 h;
+#pragma unroll
+        for (int b = 0; b < 8; ++b) h[b] = (_Float16)v[8 * d + b];
+        *reinterpret_cast<h8*>(dst + 8 * d) = h;
+      }
+    }
+  }
+}
+
 }  // namespace jf
+
+extern "C" int32_t jf_dequantize_block(const int8_t* q, const float* s, int64_t rows, int64_t cols, int32_t block,
+                                       void* out, int32_t out_dtype, int64_t ldo, void* stream) {
+  using namespace jf;
+  if (!q || !s || !out) return JF_ERR_NULL;
+  if (out_dtype != 0 && out_dtype != 1) return JF_ERR_DTYPE;
+  if (!valid_block(block)) return JF_ERR_BLOCK;
+  if (!valid_dim(rows, block) || !valid_dim(cols, block) || ldo < cols) return JF_ERR_SHAPE;
+  if (!aligned16(q) || !aligned4(s) || !aligned16(out) || (ldo % 8)) return JF_ERR_ALIGN;
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  const int64_t total = rows * (cols / 16);
+  const unsigned grid = (unsigned)((total + 255) / 256 < 8192 ? (total + 255) / 256 : 8192);
+  if (out_dtype == 0)
+    hipLaunchKernelGGL((dequantize_kernel<float>), dim3(grid), dim3(256), 0, st, q, s, (int)rows, (int)cols, (int)block,
+                       static_cast<float*>(out), ldo);
+  else
+    hipLaunchKernelGGL((dequantize_kernel<_Float16>), dim3(grid), dim3(256), 0, st, q, s, (int)rows, (int)cols, (int)block,
+                       static_cast<_Float16*>(out), ldo);
+  return launch_status();
+}
 
 extern "C" int32_t jf_quantize_block(const void* x, int32_t x_dtype, int64_t rows, int64_t cols, int64_t ldx,
                                      int32_t block, int8_t* q, int64_t ldq, float* s, int8_t* qT, int64_t ldqT,

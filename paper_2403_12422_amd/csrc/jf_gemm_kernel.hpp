@@ -165,7 +165,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN, WMIN) gemm_kernel(const GemmAr
   // four waves (one per compute unit), whose barriers are the most expensive, and for the one-sub-block waves at
   // B = 64 (a stage must hold an even number of sub-block x K-block units); 64 otherwise, which lets three
   // workgroups with a ring of three stages share the LDS of a compute unit.
-  constexpr int KC = (B == 128 || (WGM * WGN > 4 && WM * WN < 4) || WM * WN >= 8 || (B == 64 && WM * WN == 1)) ? 128 : 64;
+  constexpr int KC = (B == 128 || (WGM * WGN > 4 && WM * WN < 4) || (B == 64 && WM * WN == 1)) ? 128 : 64;
   constexpr int SPS = KC / 32;  // MFMA K steps per stage
   constexpr int NTILE = WM * WN;
   typedef TileLayout<TM, AK, KC> LA;
@@ -594,7 +594,7 @@ static void launch_cfg(const GemmArgs& a, hipStream_t st) {
   // resident waves per SIMD the register allocation has to allow: 3 for the 2x2 wave tile (three
   // 128x128 workgroups share a compute unit), the waves of the one workgroup per compute unit for the big
   // workgroups (2 for eight waves, 3 for nine or twelve), 4 for the 64x64 tiles
-  constexpr int WMIN = (WM * WN >= 8) ? 1 : (WM * WN >= 4 && WGM * WGN == 8) ? 2 : (WM * WN >= 4) ? 3 : (WGM * WGN > 8 ? 3 : (WGM * WGN > 4 ? 2 : 4));
+  constexpr int WMIN = (WM * WN >= 4 && WGM * WGN == 8) ? 2 : (WM * WN >= 4) ? 3 : (WGM * WGN > 8 ? 3 : (WGM * WGN > 4 ? 2 : 4));
   const int tiles = ((a.M + TM - 1) / TM) * ((a.Nn + TN - 1) / TN);
   hipLaunchKernelGGL((gemm_kernel<B, WM, WN, WGM, WGN, AK, BK, DUMP, WMIN>), dim3(tiles), dim3(64 * WGM * WGN), 0, st, a);
 }
@@ -622,18 +622,17 @@ static ShapeCost shape_cost(const GemmArgs& a, int tm, int tn, int waves, int ti
 }
 template <int B, bool AK, bool BK, bool DUMP>
 static void launch_shape(const GemmArgs& a, hipStream_t st) {
-  if (g_forced_shape == 5) {
-    launch_cfg<B, 4, 2, 2, 2, AK, BK, DUMP>(a, st);
-    return;
-  }
   if (g_forced_shape == 6) {
     launch_cfg<B, 2, 2, 4, 2, AK, BK, DUMP>(a, st);
     return;
   }
   if constexpr (B == 128) {
-    // 128x128 tile, eight waves of 2x1 sub-blocks: two waves per SIMD with one workgroup per compute unit, so
-    // that the MFMA chains of one wave run under the folds of the other
-    launch_cfg<B, 2, 1, 2, 4, AK, BK, DUMP>(a, st);
+    // Eight waves per workgroup, one workgroup per compute unit.  256x128 tile (waves of 2x2 sub-blocks): a
+    // third less L2 -> LDS traffic per MFMA, measured 10 % faster on every large shape; outputs with fewer
+    // than 256 such tiles take the 128x128 tile (waves of 2x1 sub-blocks) so that every compute unit has work.
+    const int64_t big_tiles = (int64_t)((a.M + 255) / 256) * ((a.Nn + 127) / 128);
+    if (big_tiles >= 256 && g_forced_shape != 1) launch_cfg<B, 2, 2, 4, 2, AK, BK, DUMP>(a, st);
+    else launch_cfg<B, 2, 1, 2, 4, AK, BK, DUMP>(a, st);
   } else if constexpr (B == 64) {
     const bool big = g_forced_shape ? g_forced_shape != 4
                                     : shape_cost(a, 128, 128, 4, 4).cycles <= shape_cost(a, 64, 64, 4, 1).cycles;

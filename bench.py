@@ -47,6 +47,9 @@ def parse_args():
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the default step: time fwd/dgrad/wgrad over the large-GEMM sweep (config 5: "
                          "M=N=K in {2048,4096,8192} and tokens 16384 x LLaMA-7B linears, block 32/64/128)")
+    ap.add_argument("--block-layer", action="store_true",
+                    help="instead of the default step: time one GPT-2-large-shaped transformer block (config 4), forward + "
+                         "backward, INT8 data flow between the layers, stock FP16 attention in between")
     ap.add_argument("--sweep-blocks", type=str, default="32,64,128")
     ap.add_argument("--sweep-shape", type=int, default=0, help="force a GEMM tile shape in the sweep (test hook)")
     ap.add_argument("--sweep-only", type=str, default="", help="run one sweep shape only, as tokens,in,out")
@@ -185,6 +188,103 @@ def sweep(args):
         "peak_TOPS": INT8_MFMA_PEAK_TOPS, "sweep": records}), flush=True)
 
 
+def block_layer(args):
+    """Config 4: one GPT-2-large-shaped transformer block (hidden 1280, 20 heads, FFN 5120, 8 x 1024 tokens, block 32),
+    forward + backward with the INT8 data flow between the layers; no bias, no dropout.  The attention core is the
+    stock torch FP16 scaled_dot_product_attention (forward and autograd backward); it is timed on its own as well and
+    its time is taken out of the INT8 figure.  966.4 GOP of INT8 linear work per step."""
+    import torch
+
+    import paper_2403_12422_amd as jf
+
+    dev = torch.device("cuda:0")
+    B, batch, seq, H, heads, F = 32, 8, 1024, 1280, 20, 5120
+    N = batch * seq
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(240312422 + 4)
+    rnd = lambda r, c, sd: torch.randn((r, c), generator=gen, device=dev, dtype=torch.float32) * sd
+    x = rnd(N, H, 1.0)
+    x[:, torch.randperm(H, generator=gen, device=dev)[:13]] *= 20.0
+    Q = lambda t: jf.jf_quantize_block(t, B)
+    (X, SX), (Wq, SWq), (Wo, SWo), (W1, SW1), (W2, SW2), (dY, SdY) = (
+        Q(t) for t in (x, rnd(3 * H, H, 0.02), rnd(H, H, 0.02), rnd(F, H, 0.02), rnd(H, F, 0.02), rnd(N, H, 1e-3)))
+    vec = lambda m, sd: (m + sd * torch.randn((H,), generator=gen, device=dev, dtype=torch.float32))
+    g1, b1, g2, b2 = vec(1.0, 0.1), vec(0.0, 0.1), vec(1.0, 0.1), vec(0.0, 0.1)
+    ws = torch.empty((max(16, jf.jf_workspace_bytes(7, N, H, 0, B)),), dtype=torch.uint8, device=dev)
+
+    def heads_view(t16):
+        return t16.view(batch, seq, heads, H // heads).transpose(1, 2)
+
+    def attention(qkv16, grad16=None):
+        q, k, v = (heads_view(qkv16[:, i * H:(i + 1) * H]) for i in range(3))
+        if grad16 is None:
+            o = torch.nn.functional.scaled_dot_product_attention(q, k, v, is_causal=True)
+            return o.transpose(1, 2).reshape(N, H).contiguous(), None
+        q, k, v = (t.detach().requires_grad_(True) for t in (q, k, v))
+        o = torch.nn.functional.scaled_dot_product_attention(q, k, v, is_causal=True)
+        o.backward(heads_view(grad16))
+        dqkv = torch.cat([t.grad.transpose(1, 2).reshape(N, H) for t in (q, k, v)], dim=1).contiguous()
+        return None, dqkv
+
+    def step():
+        # forward
+        A1, SA1, mean1, rstd1 = jf.jf_layernorm_q(X, SX, g1, b1, 1e-5, B)
+        QKV, SQKV, _ = jf.jf_linear_fwd(A1, SA1, Wq, SWq, B)
+        qkv16 = jf.jf_dequantize_block(QKV, SQKV, B, torch.float16)
+        att16, _ = attention(qkv16)
+        AT, SAT = jf.jf_quantize_block(att16, B)
+        P, SP, _ = jf.jf_linear_fwd(AT, SAT, Wo, SWo, B)
+        R1, SR1, rm, rq = jf.jf_add_q(X, SX, P, SP, B, want_partials=True)
+        A2, SA2, mean2, rstd2 = jf.jf_layernorm_q_partials(R1, SR1, rm, rq, g2, b2, 1e-5, B)
+        H1, SH1, _ = jf.jf_linear_fwd(A2, SA2, W1, SW1, B)
+        GE, SGE = jf.jf_gelu_q(H1, SH1, B)
+        H2, SH2, _ = jf.jf_linear_fwd(GE, SGE, W2, SW2, B)
+        jf.jf_add_q(R1, SR1, H2, SH2, B)
+        # backward
+        dGE, SdGE, _ = jf.jf_linear_dgrad(dY, SdY, W2, SW2, B)
+        jf.jf_linear_wgrad(dY, SdY, GE, SGE, B)
+        dH1, SdH1 = jf.jf_gelu_q_bwd(dGE, SdGE, H1, SH1, B)
+        dA2, SdA2, _ = jf.jf_linear_dgrad(dH1, SdH1, W1, SW1, B)
+        jf.jf_linear_wgrad(dH1, SdH1, A2, SA2, B)
+        dR1a, SdR1a, _, _ = jf.jf_layernorm_q_bwd(dA2, SdA2, R1, SR1, g2, mean2, rstd2, B, workspace=ws)
+        dR1, SdR1 = jf.jf_add_q(dY, SdY, dR1a, SdR1a, B)
+        dAT, SdAT, _ = jf.jf_linear_dgrad(dR1, SdR1, Wo, SWo, B)
+        jf.jf_linear_wgrad(dR1, SdR1, AT, SAT, B)
+        dat16 = jf.jf_dequantize_block(dAT, SdAT, B, torch.float16)
+        _, dqkv16 = attention(qkv16, dat16)
+        dQKV, SdQKV = jf.jf_quantize_block(dqkv16, B)
+        dA1, SdA1, _ = jf.jf_linear_dgrad(dQKV, SdQKV, Wq, SWq, B)
+        jf.jf_linear_wgrad(dQKV, SdQKV, A1, SA1, B)
+        dXa, SdXa, _, _ = jf.jf_layernorm_q_bwd(dA1, SdA1, X, SX, g1, mean1, rstd1, B, workspace=ws)
+        jf.jf_add_q(dR1, SdR1, dXa, SdXa, B)
+        return qkv16, dat16
+
+    def timed(fn, steps, warmup):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps * 1e3
+
+    steps, warmup = min(args.steps, 50), min(args.warmup, 10)
+    qkv16, dat16 = step()
+    ms_block = timed(step, steps, warmup)
+    ms_attn = timed(lambda: (attention(qkv16), attention(qkv16, dat16)), steps, warmup)
+    gop = 2.0 * 3 * N * H * (3 * H + H + F + F) * 1e-9      # fwd + dgrad + wgrad of the four linears
+    ms_int8 = ms_block - ms_attn
+    print(json.dumps({
+        "metric": "per-block INT8 linear TOPS (fwd+dgrad+wgrad), transformer block with the INT8 data flow",
+        "value": round(gop / ms_int8, 3), "unit": "TOPS (966.4 GOP of INT8 linear work / time of the INT8 operators of one block step)",
+        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": round(ms_block, 4), "dtype": "int8", "data": "synthetic",
+        "config": {"workload": "config 4: GPT-2-large-shaped block, hidden 1280, 20 heads, FFN 5120, 8x1024 tokens, block 32, "
+                               "forward + backward, no bias, no dropout; outputs allocated by torch inside the step"},
+        "ms_attention_fp16_fwd_bwd": round(ms_attn, 4), "ms_int8_operators": round(ms_int8, 4),
+        "int8_linear_gop": round(gop, 1), "frac_int8_mfma_peak": round(gop / ms_int8 / INT8_MFMA_PEAK_TOPS, 4)}), flush=True)
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -205,6 +305,9 @@ def main():
     torch.cuda.set_device(dev)
     if args.sweep:
         sweep(args)
+        return
+    if args.block_layer:
+        block_layer(args)
         return
     N, C, D, B = args.tokens, args.in_features, args.out_features, args.block
 

@@ -162,9 +162,10 @@ __global__ void __launch_bounds__(64 * WGM * WGN, WMIN) gemm_kernel(const GemmAr
   constexpr int TM = 32 * WM * WGM, TN = 32 * WN * WGN;
   constexpr int KPB = B / 32;  // MFMA K steps per quantization block
   // K bytes per stage: 128 when a stage has to hold a whole B = 128 block, for the workgroups of more than
-  // four waves (one per compute unit), whose barriers are the most expensive, and for the one-sub-block waves at
-  // B = 64 (a stage must hold an even number of sub-block x K-block units); 64 otherwise, which lets three
-  // workgroups with a ring of three stages share the LDS of a compute unit.
+  // four waves of fewer than four sub-blocks each (one workgroup per compute unit, whose barriers are the most
+  // expensive), and for the one-sub-block waves at B = 64 (a stage must hold an even number of sub-block x
+  // K-block units); 64 otherwise, which lets three workgroups with a ring of three stages share the LDS of a
+  // compute unit.
   constexpr int KC = (B == 128 || (WGM * WGN > 4 && WM * WN < 4) || (B == 64 && WM * WN == 1)) ? 128 : 64;
   constexpr int SPS = KC / 32;  // MFMA K steps per stage
   constexpr int NTILE = WM * WN;
@@ -176,7 +177,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN, WMIN) gemm_kernel(const GemmAr
   constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
 
   // Stages in the LDS ring: one being read, the rest in flight.  Tiles that leave a compute unit to a single
-  // workgroup (more than four waves) take a ring of four, the others a ring of three.
+  // workgroup (more than four waves) take a ring of four if that fits the LDS, the others a ring of three.
   constexpr int NBUF = (NW > 4 && 4 * STAGE_BYTES <= 156 * 1024) ? 4 : 3;
   static_assert(NBUF * STAGE_BYTES <= 160 * 1024, "the ring must fit the LDS of a compute unit");
   // One LDS variable per ring slot: the compiler tracks direct-to-LDS loads per variable, so a read of
@@ -198,7 +199,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN, WMIN) gemm_kernel(const GemmAr
   // works on one contiguous run of tiles, and order the tiles in groups of GROUP_M tile rows, column by column
   // inside a group: the workgroups that are resident on an XCD at the same time then form a compact patch
   // (8 tile rows x a few tile columns) that re-reads few distinct operand tiles from that XCD's L2.
-  constexpr int GROUP_M = 8;
+  constexpr int GROUP_M = TM >= 256 ? 4 : 8;
   const int ntiles = gridDim.x, tiles_n = (g.Nn + TN - 1) / TN, tiles_m = (g.M + TM - 1) / TM;
   const int xcd = blockIdx.x & 7, idx = blockIdx.x >> 3;
   const int tile = xcd * (ntiles >> 3) + min(xcd, ntiles & 7) + idx;

@@ -179,6 +179,32 @@ def test_linear_k_loop_every_stage_count(shape):
         jf.jf_debug_set_gemm_shape(0)
 
 
+@pytest.mark.parametrize("block,shape", [(64, 1), (64, 4), (128, 1), (128, 6)])
+def test_linear_k_loop_large_blocks(block, shape):
+    """Blocks 64 and 128 run a chain of MFMAs per quantization block and, for waves of 2x2 sub-blocks, refill
+    the fragment registers from the next stage while the current one is still being folded.  Sweep the number
+    of K blocks so that the prologue, the main passes and every tail length run, for all three operand layouts;
+    FP32 accumulators must match the oracle's bit for bit."""
+    jf.jf_debug_set_gemm_shape(shape)
+    try:
+        for nkb in list(range(1, 11)) + [13, 16, 17]:
+            n = block * nkb
+            say(f"block {block} tile shape {shape}: {nkb} K blocks")
+            (X, SX), (W, SW), (dY, SdY) = _quantized_layer(4200 + block + nkb, 256, n, 256, block)
+            Xd, SXd, Wd, SWd = map(dev, (X, SX, W, SW))
+            np.testing.assert_array_equal(host(jf.jf_linear_fwd(Xd, SXd, Wd, SWd, block, want_f32=True)[2]),
+                                          oracle.linear_fwd(X, SX, W, SW, block)[2])
+            # dgrad contracts over D, wgrad over N: build layers whose D resp. N is the swept length
+            (X2, SX2), (W2, SW2), (dY2, SdY2) = _quantized_layer(4300 + block + nkb, 256, 256, n, block)
+            np.testing.assert_array_equal(host(jf.jf_linear_dgrad(*map(dev, (dY2, SdY2, W2, SW2)), block, want_f32=True)[2]),
+                                          oracle.linear_dgrad(dY2, SdY2, W2, SW2, block)[2])
+            (X3, SX3), (W3, SW3), (dY3, SdY3) = _quantized_layer(4400 + block + nkb, n, 256, 256, block)
+            np.testing.assert_array_equal(host(jf.jf_linear_wgrad(*map(dev, (dY3, SdY3, X3, SX3)), block, want_f32=True)[2]),
+                                          oracle.linear_wgrad(dY3, SdY3, X3, SX3, block)[2])
+    finally:
+        jf.jf_debug_set_gemm_shape(0)
+
+
 def test_linear_zero_blocks_and_run_to_run_stability():
     block, N, C, D = 32, 128, 128, 128
     (X, SX), (W, SW), _ = _quantized_layer(3100, N, C, D, block)

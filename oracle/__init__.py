@@ -258,3 +258,20 @@ def layernorm_q_stats(X, SX, gamma, beta, mean, rstd, block=32):
     _check(_load().oracle_layernorm_q_stats(_p(X), _p(SX), _p(gamma), _p(beta), _p(mean), _p(rstd), _I64(N), _I64(C),
                                             _I32(block), _p(Y), _p(SY), _p(f)), "layernorm_q_stats")
     return Y, SY, f
+
+
+def dropout_q(X, SX, mask_bits, p, block=32):
+    """App. A (Dropout) + Alg. 2: y = x * m / (1 - p); the backward pass is the same call on the gradient.
+
+    mask_bits: (N, C/8) uint8, bit (c mod 8) of byte c/8 of a row belongs to column c.
+    Returns (codes, scales, float64 pre-quantization values)."""
+    X, SX = _i8(X), _f32(SX)
+    mask_bits = np.ascontiguousarray(mask_bits)
+    N, C = X.shape
+    assert mask_bits.dtype == np.uint8 and mask_bits.shape == (N, C // 8)
+    Y = np.empty((N, C), np.int8)
+    SY = np.empty((N // block, C // block), np.float32)
+    f = np.empty((N, C), np.float64)
+    _check(_load().oracle_dropout_q(_p(X), _p(SX), _p(mask_bits), ctypes.c_float(p), _I64(N), _I64(C), _I32(block),
+                                    _p(Y), _p(SY), _p(f)), "dropout_q")
+    return Y, SY, f

@@ -509,3 +509,26 @@ int oracle_layernorm_q_stats(const int8_t* X, const float* SX, const float* gamm
   free(y);
   return rc;
 }
+
+/* App. A, Dropout: Drop(x) = x o m / (1 - p) with a 0/1 mask m, and dDrop/dx = m / (1 - p): the backward pass
+ * applies the same operator, with the same mask, to the upstream gradient.  The mask is an input (the random
+ * draw is not part of the operator): bit (c mod 8) of byte mask[i * C/8 + c/8] belongs to element (i, c).
+ * x is the dequantized INT8 input; the result goes through Alg. 2's quantize step. */
+int oracle_dropout_q(const int8_t* X, const float* SX, const uint8_t* mask, float p, int64_t N, int64_t C, int block,
+                     int8_t* Y, float* SY, double* y_f) {
+  if (bad_shape(N, C, block)) return ORACLE_ERR_SHAPE;
+  if (!(p >= 0.0f && p < 1.0f)) return ORACLE_ERR_SHAPE;
+  double* y = (double*)malloc(sizeof(double) * N * C);
+  if (!y) return 3;
+  oracle_dequantize(X, SX, N, C, block, y);
+  const double keep_scale = 1.0 / (1.0 - (double)p);
+  for (int64_t i = 0; i < N; ++i)
+    for (int64_t c = 0; c < C; ++c) {
+      const int m = (mask[i * (C / 8) + c / 8] >> (c % 8)) & 1;
+      y[i * C + c] = m ? y[i * C + c] * keep_scale : 0.0;
+    }
+  if (y_f) memcpy(y_f, y, sizeof(double) * N * C);
+  int rc = quantize_from_double(y, N, C, block, Y, SY);
+  free(y);
+  return rc;
+}

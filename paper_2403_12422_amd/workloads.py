@@ -53,6 +53,13 @@ def layernorm_case(seed_offset, N, C, outlier_fraction=0.01, outlier_factor=20.0
     return X, gamma, beta, dY
 
 
+def dropout_mask_bits(g, N, C, p):
+    """Keep-mask of a dropout layer with drop probability p, packed 8 columns per byte (column c of a row is bit
+    c % 8 of byte c // 8).  Returns (bits (N, C/8) uint8, mask (N, C) bool)."""
+    keep = g.random((N, C), dtype=np.float32) >= np.float32(p)
+    return np.packbits(keep, axis=1, bitorder="little"), keep
+
+
 # The five benchmark configurations (shapes only; see the design notes for the value recipe).
 CONFIGS = {
     "cfg1_single_fwd": dict(N=256, C=256, D=256, block=32, act_std=1.0, w_std=1.0),

@@ -458,3 +458,36 @@ def test_layernorm_from_statistics_matches_torch_and_the_self_statistics_operato
     _, _, f2 = oracle.layernorm_q_stats(X, SX, gamma, beta, m2, r2, block)
     np.testing.assert_allclose(f2, (xd - m2[:, None].astype(np.float64)) * r2[:, None].astype(np.float64) * gamma + beta,
                                rtol=1e-12, atol=1e-12)
+
+
+# --------------------------------------------------------------------------- Dropout (App. A)
+def test_dropout_against_numpy_identity_zero_and_linearity():
+    block, N, C, p = 32, 64, 96, 0.1
+    g = workloads.rng(740)
+    x = workloads.gaussian(g, N, C, 1.0)
+    X, SX = oracle.quantize_block(x, block)
+    xd = oracle.dequantize(X, SX, block)
+    bits, keep = workloads.dropout_mask_bits(g, N, C, p)
+    assert 0.8 < keep.mean() < 0.97
+    Y, SY, f = oracle.dropout_q(X, SX, bits, p, block)
+    # library arithmetic on the dequantized tensor; p is an FP32 number
+    np.testing.assert_allclose(f, np.where(keep, xd / (1.0 - float(np.float32(p))), 0.0), rtol=1e-15, atol=0)
+    q, s = oracle.quantize_block(f.astype(np.float32), block)
+    np.testing.assert_array_equal(Y, q)
+    np.testing.assert_array_equal(SY, s)
+    # the bit order: dropping exactly column 9 zeroes exactly that column
+    only9 = np.ones((N, C), bool)
+    only9[:, 9] = False
+    _, _, f9 = oracle.dropout_q(X, SX, np.packbits(only9, axis=1, bitorder="little"), 0.0, block)
+    assert np.all(f9[:, 9] == 0) and np.array_equal(np.delete(f9, 9, axis=1), np.delete(xd, 9, axis=1))
+    # p = 0 with everything kept is the identity on the codes; everything dropped gives zero codes and zero scales
+    ones = np.full((N, C // 8), 255, np.uint8)
+    Y1, SY1, _ = oracle.dropout_q(X, SX, ones, 0.0, block)
+    np.testing.assert_array_equal(Y1, X)
+    np.testing.assert_allclose(SY1, SX, rtol=2e-7)
+    Y0, SY0, _ = oracle.dropout_q(X, SX, np.zeros((N, C // 8), np.uint8), p, block)
+    assert not Y0.any() and not SY0.any()
+    # the operator is linear in x, so it is its own backward: d/dx sum(w * Drop(x)) = Drop(w) element-wise
+    assert 0.9 < f.sum() / (xd * keep).sum() * (1 - p) < 1.1
+    with pytest.raises(ValueError):
+        oracle.dropout_q(X, SX, bits, 1.0, block)

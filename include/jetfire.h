@@ -182,6 +182,16 @@ int32_t jf_add_q(const int8_t* X1, const float* S1, const int8_t* X2, const floa
                  int32_t block, int8_t* Y, float* SY, float* row_mean, float* row_sumsq, void* stream);
 
 /*
+ * INT8 Dropout (App. A): Y = Q(X o m / (1 - p)) on the dequantized input.  The
+ * keep mask m is an input (the random draw is the caller's): mask_bits is
+ * N x (C/8) bytes, row-major, bit (c mod 8) of byte c/8 of a row belongs to
+ * column c; 2-byte aligned.  0 <= p < 1 (else JF_ERR_SHAPE).  The backward
+ * pass, dX = dY o m / (1 - p), is the same call on the upstream gradient.
+ */
+int32_t jf_dropout_q(const int8_t* X, const float* SX, const uint8_t* mask_bits, float p, int64_t N, int64_t C,
+                     int32_t block, int8_t* Y, float* SY, void* stream);
+
+/*
  * INT8 LayerNorm backward (standard LayerNorm gradient on dequantized
  * operands).  xhat = (x - mean) rstd, ghat = dY * gamma:
  *   dX = rstd (ghat - mean_C(ghat) - xhat mean_C(ghat xhat)),

@@ -11,6 +11,7 @@ from .binding import (  # noqa: F401
     jf_debug_linear_partials,
     jf_debug_set_gemm_shape,
     jf_dequantize_block,
+    jf_dropout_q,
     jf_gelu_q,
     jf_gelu_q_bwd,
     jf_layernorm_q,

@@ -26,6 +26,7 @@ _SIGNATURES = {
     "jf_gelu_q_bwd": (_I32, [_P, _P, _P, _P, _I64, _I64, _I32, _P, _P, _P]),
     "jf_layernorm_q": (_I32, [_P, _P, _P, _P, _F32, _I64, _I64, _I32, _P, _P, _P, _P, _P]),
     "jf_layernorm_q_partials": (_I32, [_P, _P, _P, _P, _P, _P, _F32, _I64, _I64, _I32, _P, _P, _P, _P, _P]),
+    "jf_dropout_q": (_I32, [_P, _P, _P, _F32, _I64, _I64, _I32, _P, _P, _P]),
     "jf_add_q": (_I32, [_P, _P, _P, _P, _I64, _I64, _I32, _P, _P, _P, _P, _P]),
     "jf_layernorm_q_bwd": (_I32, [_P, _P, _P, _P, _P, _P, _P, _I64, _I64, _I32, _P, _P, _P, _P, _P, _SZ, _P]),
     "jf_debug_linear_partials": (_I32, [_I32, _P, _P, _I64, _I64, _I64, _I32, _I64, _P, _P]),
@@ -225,6 +226,17 @@ def jf_layernorm_q_partials(X, SX, row_mean, row_sumsq, gamma, beta, eps=1e-5, b
                                                   _ptr(beta), eps, N, C, block, _ptr(Y), _ptr(SY), _ptr(mean),
                                                   _ptr(rstd), _stream()))
     return Y, SY, mean, rstd
+
+
+def jf_dropout_q(X, SX, mask_bits, p, block=32, out=None):
+    """Y = Q(X * m / (1 - p)); mask_bits (N, C/8) uint8, bit c % 8 of byte c // 8 of a row is column c's keep bit."""
+    _dev(X, torch.int8, 2), _dev(SX, torch.float32, 2), _dev(mask_bits, torch.uint8, 2)
+    N, C = X.shape
+    if tuple(mask_bits.shape) != (N, C // 8):
+        raise JetfireError(2, "mask_bits must be (N, C / 8)")
+    Y, SY = out if out is not None else (torch.empty_like(X), torch.empty_like(SX))
+    _check(load_library().jf_dropout_q(_ptr(X), _ptr(SX), _ptr(mask_bits), p, N, C, block, _ptr(Y), _ptr(SY), _stream()))
+    return Y, SY
 
 
 def jf_add_q(X1, S1, X2, S2, block=32, want_partials=False, out=None):

@@ -253,6 +253,55 @@ __global__ void __launch_bounds__(256) add_kernel(const int8_t* __restrict__ X1,
 }
 
 // ------------------------------------------------------------------------------------------------
+// Dropout (App. A): y = x o m / (1 - p) on the dequantized input, re-quantized per block; the keep mask m is
+// an input, packed 8 columns per byte (bit c % 8 of byte c / 8 of a row).  The backward pass is the same
+// operator on the upstream gradient.  Same tiling as GELU; a lane's 16 columns are two mask bytes.
+template <int B>
+__global__ void __launch_bounds__(256) dropout_kernel(const int8_t* __restrict__ X, const float* __restrict__ SX,
+                                                       const uint8_t* __restrict__ mask, float keep_scale, int rows,
+                                                       int cols, int8_t* __restrict__ Y, float* __restrict__ SY) {
+  constexpr int P = B / 32;
+  __shared__ float s_amax[4][4];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int ch = lane & 7, rsub = lane >> 3;
+  const int col = blockIdx.x * 128 + 16 * ch;
+  const int r0 = blockIdx.y * B + wave * (B / 4);
+  const bool col_ok = col < cols;
+  const int lc = cols / B, bi = blockIdx.y;
+
+  float y[P][16];
+  float m = 0.0f;
+  if (col_ok) {
+    const float k = SX[(int64_t)bi * lc + col / B] * keep_scale;
+    const float k128 = -128.0f * k;  // the unpacked codes carry +128
+#pragma unroll
+    for (int p = 0; p < P; ++p) {
+      const int row = r0 + 8 * p + rsub;
+      float u[16];
+      unpack16_biased(*reinterpret_cast<const uint4*>(X + (int64_t)row * cols + col), u);
+      const uint32_t bits = *reinterpret_cast<const uint16_t*>(mask + (int64_t)row * (cols / 8) + col / 8);
+#pragma unroll
+      for (int e = 0; e < 16; ++e) y[p][e] = ((bits >> e) & 1u) ? __builtin_fmaf(u[e], k, k128) : 0.0f;
+#pragma unroll
+      for (int e = 0; e < 16; e += 4) m = amax4(m, y[p][e], y[p][e + 1], y[p][e + 2], y[p][e + 3]);
+    }
+  }
+  m = strip_block_max<B>(m);
+  if ((lane & 57) == 0) s_amax[wave][ch >> 1] = m;
+  __syncthreads();
+  m = fmaxf(fmaxf(s_amax[0][ch >> 1], s_amax[1][ch >> 1]), fmaxf(s_amax[2][ch >> 1], s_amax[3][ch >> 1]));
+  float scale, inv;
+  block_scale(m, scale, inv);
+  if (!col_ok) return;
+  if (wave == 0 && rsub == 0 && (col % B) == 0) SY[(int64_t)bi * lc + col / B] = scale;
+#pragma unroll
+  for (int p = 0; p < P; ++p) {
+    const int row = r0 + 8 * p + rsub;
+    *reinterpret_cast<uint4*>(Y + (int64_t)row * cols + col) = quantize16(y[p], inv);
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
 // LayerNorm.  One workgroup of four waves owns B rows and all C columns; wave w owns rows
 // [w*B/4, (w+1)*B/4).  Lane l of a wave owns the 16-byte chunks l, l+64, ... of each of its rows, so a
 // row is read as contiguous 1 KB runs and per-column quantities (gamma, beta, column sums) stay in
@@ -945,6 +994,24 @@ extern "C" int32_t jf_layernorm_q_partials(const int8_t* X, const float* SX, con
   if (!row_mean || !row_sumsq) return JF_ERR_NULL;
   if (!jf::aligned4(row_mean) || !jf::aligned4(row_sumsq)) return JF_ERR_ALIGN;
   return layernorm_fwd(X, SX, row_mean, row_sumsq, gamma, beta, eps, N, C, block, Y, SY, mean, rstd, stream);
+}
+
+extern "C" int32_t jf_dropout_q(const int8_t* X, const float* SX, const uint8_t* mask_bits, float p, int64_t N, int64_t C,
+                                int32_t block, int8_t* Y, float* SY, void* stream) {
+  using namespace jf;
+  int32_t rc = check_eltwise(X, SX, Y, SY, N, C, block);
+  if (rc != JF_OK) return rc;
+  if (!mask_bits) return JF_ERR_NULL;
+  if (!(p >= 0.0f && p < 1.0f)) return JF_ERR_SHAPE;
+  if (reinterpret_cast<uintptr_t>(mask_bits) & 1u) return JF_ERR_ALIGN;
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  const dim3 grid((unsigned)((C + 127) / 128), (unsigned)(N / block));
+  const float keep_scale = (float)(1.0 / (1.0 - (double)p));
+  const int rows = (int)N, cols = (int)C;
+  if (block == 32) hipLaunchKernelGGL((dropout_kernel<32>), grid, dim3(256), 0, st, X, SX, mask_bits, keep_scale, rows, cols, Y, SY);
+  else if (block == 64) hipLaunchKernelGGL((dropout_kernel<64>), grid, dim3(256), 0, st, X, SX, mask_bits, keep_scale, rows, cols, Y, SY);
+  else hipLaunchKernelGGL((dropout_kernel<128>), grid, dim3(256), 0, st, X, SX, mask_bits, keep_scale, rows, cols, Y, SY);
+  return launch_status();
 }
 
 extern "C" int32_t jf_add_q(const int8_t* X1, const float* S1, const int8_t* X2, const float* S2, int64_t N, int64_t C,

@@ -68,6 +68,10 @@ def test_argument_validation_returns_codes_without_launching():
     assert lib.jf_gelu_q_bwd(None, FAKE, FAKE, FAKE, 64, 64, 32, FAKE, FAKE, None) == 1
     assert lib.jf_layernorm_q(FAKE, FAKE, None, FAKE, ctypes.c_float(1e-5), 64, 64, 32, FAKE, FAKE, FAKE, FAKE, None) == 1
     assert lib.jf_layernorm_q_bwd(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 64, 64, 32, FAKE, FAKE, FAKE, FAKE, FAKE, 16, None) == 5
+    assert lib.jf_dropout_q(FAKE, FAKE, None, ctypes.c_float(0.1), 64, 64, 32, FAKE, FAKE, None) == 1
+    assert lib.jf_dropout_q(FAKE, FAKE, FAKE, ctypes.c_float(1.0), 64, 64, 32, FAKE, FAKE, None) == 2
+    assert lib.jf_dequantize_block(FAKE, FAKE, 64, 64, 32, FAKE, 2, 64, None) == 7
+    assert lib.jf_dequantize_block(FAKE, FAKE, 64, 64, 32, FAKE, 1, 32, None) == 2
     assert lib.jf_add_q(FAKE, FAKE, None, FAKE, 64, 64, 32, FAKE, FAKE, None, None, None) == 1
     assert lib.jf_add_q(FAKE, FAKE, FAKE, FAKE, 64, 64, 32, FAKE, FAKE, FAKE, None, None) == 1      # partials come together
     assert lib.jf_add_q(FAKE, FAKE, FAKE, FAKE, 64, 80, 32, FAKE, FAKE, None, None, None) == 2

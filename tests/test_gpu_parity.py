@@ -377,6 +377,23 @@ def test_add_and_layernorm_from_partials(block, N, C):
     _check_eltwise("layernorm from partials", Z, SZ, oZ, oSZ, oz, block)
 
 
+# --------------------------------------------------------------------------- Dropout
+@pytest.mark.parametrize("block,N,C,p", [(32, 96, 352, 0.1), (64, 128, 192, 0.5), (128, 256, 384, 0.0), (32, 4096, 3072, 0.1)])
+def test_dropout_fwd_and_as_its_own_backward(block, N, C, p):
+    say(f"dropout block={block} {N}x{C} p={p}")
+    g = workloads.rng(8000 + block + N)
+    x, gr = workloads.gelu_case(8100 + block, N, C)
+    bits, keep = workloads.dropout_mask_bits(g, N, C, p)
+    keep[:block, :block] = False                                # a block that is dropped entirely
+    bits = np.packbits(keep, axis=1, bitorder="little")
+    for name, t in (("dropout fwd", x), ("dropout bwd", gr)):
+        X, SX = oracle.quantize_block(t, block)
+        Y, SY = jf.jf_dropout_q(dev(X), dev(SX), dev(bits), p, block)
+        oY, oSY, of = oracle.dropout_q(X, SX, bits, p, block)
+        _check_eltwise(name, Y, SY, oY, oSY, of, block)
+        assert not host(Y)[:block, :block].any() and host(SY)[0, 0] == 0
+
+
 # --------------------------------------------------------------------------- large-GEMM sweep (config 5)
 # Every shape of the sweep and every block size appear at least once; the full cross product would only
 # repeat the same code paths.  Each product is checked on sampled output blocks (each over the full K, FP32

@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "jetfire.h"
 
 namespace jf {
@@ -39,30 +41,68 @@ inline int64_t ln_bwd_partial_rows(int64_t N, int64_t C, int32_t block) {
 inline bool valid_dim(int64_t d, int32_t block) { return d > 0 && d <= (int64_t(1) << 24) && d % block == 0; }
 
 // -------------------------------------------------------------- device side
-// Max over the lanes whose ids differ only in the bits of `mask` (butterfly
-// over ds_bpermute; every lane of the wave must be active).
+// Cross-lane exchange for butterfly reductions without LDS traffic: the value of lane (id ^ 2^BIT) for every lane.
+// Bits 0..3 are DPP moves inside a row of 16 lanes (quad permutes, half-row mirror, row rotate by 8); bits 4 and 5
+// use the row / half-wave swap instructions of gfx950.  BIT 2 (half-row mirror, lane i <-> 7 - i) equals
+// "xor 4" only when the four lanes of every quad already hold the same value, i.e. after the steps for bits 0
+// and 1 -- every reduction below that contains bit 2 also contains bits 0 and 1 and takes them first.
+// Every lane of the wave must be active.
+template <int BIT>
+__device__ __forceinline__ int lane_xor_i32(int v) {
+  if constexpr (BIT == 0) return __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xf, 0xf, false);        // quad_perm [1,0,3,2]
+  else if constexpr (BIT == 1) return __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xf, 0xf, false);   // quad_perm [2,3,0,1]
+  else if constexpr (BIT == 2) return __builtin_amdgcn_update_dpp(0, v, 0x141, 0xf, 0xf, false);  // row_half_mirror
+  else if constexpr (BIT == 3) return __builtin_amdgcn_update_dpp(0, v, 0x128, 0xf, 0xf, false);  // row_ror:8
+  else if constexpr (BIT == 4) {
+    // odd rows of the first operand <-> even rows of the second: (r0 r0 r2 r2) and (r1 r1 r3 r3)
+    auto p = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+    return ((__lane_id() >> 4) & 1) ? (int)p[0] : (int)p[1];
+  } else {
+    // upper half of the first operand <-> lower half of the second: (lo lo) and (hi hi)
+    auto p = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+    return (__lane_id() >> 5) ? (int)p[0] : (int)p[1];
+  }
+}
+template <int BIT>
+__device__ __forceinline__ float lane_xor_f32(float v) {
+  return __builtin_bit_cast(float, lane_xor_i32<BIT>(__builtin_bit_cast(int, v)));
+}
+template <int BIT>
+__device__ __forceinline__ double lane_xor_f64(double v) {
+  const long long b = __builtin_bit_cast(long long, v);
+  const unsigned lo = (unsigned)lane_xor_i32<BIT>((int)(b & 0xffffffffll)), hi = (unsigned)lane_xor_i32<BIT>((int)(b >> 32));
+  return __builtin_bit_cast(double, ((long long)hi << 32) | (long long)lo);
+}
+
+template <int MASK, int BIT = 0, class T, class Op, class Xor>
+__device__ __forceinline__ T wave_group_reduce(T v, Op op, Xor lane_xor) {
+  static_assert(!(MASK & 4) || (MASK & 3) == 3, "the step for bit 2 needs bits 0 and 1 reduced first");
+  if constexpr (BIT < 6) {
+    if constexpr ((MASK >> BIT) & 1) v = op(v, lane_xor(v, std::integral_constant<int, BIT>()));
+    return wave_group_reduce<MASK, BIT + 1>(v, op, lane_xor);
+  } else {
+    return v;
+  }
+}
+
+// Max / sum over the lanes whose ids differ only in the bits of MASK (butterfly; every lane of the wave must be
+// active).  The summation order is fixed, so results are bit-stable.
 template <int MASK>
 __device__ __forceinline__ float wave_group_max(float v) {
-#pragma unroll
-  for (int m = 1; m < 64; m <<= 1)
-    if (MASK & m) v = fmaxf(v, __shfl_xor(v, m, 64));
-  return v;
+  return wave_group_reduce<MASK>(v, [](float a, float b) { return fmaxf(a, b); },
+                                 [](float x, auto bit) { return lane_xor_f32<decltype(bit)::value>(x); });
 }
 
 template <int MASK>
 __device__ __forceinline__ float wave_group_sum(float v) {
-#pragma unroll
-  for (int m = 1; m < 64; m <<= 1)
-    if (MASK & m) v += __shfl_xor(v, m, 64);
-  return v;
+  return wave_group_reduce<MASK>(v, [](float a, float b) { return a + b; },
+                                 [](float x, auto bit) { return lane_xor_f32<decltype(bit)::value>(x); });
 }
 
 template <int MASK>
 __device__ __forceinline__ double wave_group_sum_f64(double v) {
-#pragma unroll
-  for (int m = 1; m < 64; m <<= 1)
-    if (MASK & m) v += __shfl_xor(v, m, 64);
-  return v;
+  return wave_group_reduce<MASK>(v, [](double a, double b) { return a + b; },
+                                 [](double x, auto bit) { return lane_xor_f64<decltype(bit)::value>(x); });
 }
 
 // Eq. 1 scale of a block from its max-abs: one IEEE FP32 division; 0 for an

@@ -339,6 +339,7 @@ __global__ void __launch_bounds__(1024) layernorm_fwd_kernel(const int8_t* __res
                                                               const float* __restrict__ row_sumsq) {
   constexpr int NW = 16, RW = B / NW;
   constexpr bool KEEP = RW * NIT <= 8;
+  const double inv_cols = 1.0 / (double)cols;  // uniform: one division per wave
   extern __shared__ float s_dyn[];  // [NW][C/32] per-wave block max-abs
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int r0 = blockIdx.x * B + wave * RW;
@@ -394,11 +395,16 @@ __global__ void __launch_bounds__(1024) layernorm_fwd_kernel(const int8_t* __res
     }
     const double sum = wave_group_sum_f64<63>(ds);
     const double sq = wave_group_sum_f64<63>(dq);
-    const double mean = sum / (double)cols;
-    double var = sq / (double)cols - mean * mean;
+    // The cancellation in E[x^2] - mean^2 is taken in double; the reciprocal square root of the (FP32) result is
+    // the hardware approximation refined by one Newton step (relative error ~1e-7), which keeps the double-
+    // precision divide and square root, a few hundred cycles each, off the latency path of the kernel.
+    const double mean = sum * inv_cols;
+    double var = sq * inv_cols - mean * mean;
     var = var > 0.0 ? var : 0.0;
-    const double rstd = 1.0 / sqrt(var + (double)eps);
-    const float mu = (float)mean, rs = (float)rstd;
+    const float ve = (float)(var + (double)eps);
+    float rs = __builtin_amdgcn_rsqf(ve);
+    rs = rs * __builtin_fmaf(-0.5f * ve * rs, rs, 1.5f);
+    const float mu = (float)mean;
     if (lane == 0) {
       mean_out[r0 + r] = mu;
       rstd_out[r0 + r] = rs;

@@ -428,6 +428,13 @@ def main():
                                                         out=(dX, SdX, dgamma, dbeta)),
                           N * C * (3 + 3 * sb) + 8 * N + 12 * C),
     }
+    # the residual / dropout operators of the transformer block on the same 4096 x 3072 tensor
+    mask_bits = torch.randint(0, 256, (N, D // 8), dtype=torch.uint8, device=dev)
+    rm, rq = torch.empty((N, D // B), dtype=torch.float32, device=dev), torch.empty((N, D // B), dtype=torch.float32, device=dev)
+    ops["add"] = (lambda: jf.jf_add_q(Y, SY, H, SH, B, out=(dY, SdY)), N * D * (3 + 3 * sb))
+    ops["add_with_row_partials"] = (lambda: jf.jf_add_q(Y, SY, H, SH, B, want_partials=True, out=(dY, SdY, rm, rq)),
+                                    N * D * (3 + 3 * sb + 8.0 / B))
+    ops["dropout"] = (lambda: jf.jf_dropout_q(Y, SY, mask_bits, 0.1, B, out=(dY, SdY)), N * D * (2.125 + 2 * sb))
     memops = {}
     for name, (fn, nbytes) in ops.items():
         ms = op_ms(fn)

@@ -297,7 +297,9 @@ def _check_eltwise(name, q, s, oq, os_, of64, block):
     say(f"  {name}: {nbad} / {oq.size} codes differ by one")
 
 
-@pytest.mark.parametrize("block,N,C", [(32, 96, 352), (64, 128, 192), (128, 256, 384), (32, 4096, 3072)])
+# the last two cases are large enough for the 256-column workgroups, with a ragged last column group
+@pytest.mark.parametrize("block,N,C", [(32, 96, 352), (64, 128, 192), (128, 256, 384), (32, 4096, 3072),
+                                       (32, 32768, 1120), (64, 65536, 1088)])
 def test_gelu_fwd_bwd(block, N, C):
     say(f"gelu block={block} {N}x{C}")
     x, gr = workloads.gelu_case(5000 + block + N, N, C)

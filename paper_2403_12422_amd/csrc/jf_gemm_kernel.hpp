@@ -117,6 +117,36 @@ struct FragAddr {
   }
 };
 
+// One direct-to-LDS load of 16 bytes per lane: lane l's bytes from ubase + voff go to LDS address lds + 16*l.
+// Written out because the compiler only selects the 64-bit per-lane address form for the builtin; the form with
+// a scalar base and a 32-bit vector offset needs no address arithmetic on the vector ALU.  M0 carries the LDS
+// address and needs one wait state before the load reads it.  The load counts in vmcnt like any other; the
+// callers wait for it with s_waitcnt before the stage barrier.
+// Every direct-to-LDS load of the kernel goes through these two helpers, so the compiler itself never uses M0.
+__device__ __forceinline__ uint32_t lds_address(const int8_t* lds_tile, int lds_byte) {
+  // the tile's LDS address is taken before the byte offset is added: a cast of the sum would carry a null check
+  return __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_ptr)(lds_tile) + (uint32_t)lds_byte);
+}
+__device__ __forceinline__ void load_lds_16(const int8_t* ubase, uint32_t voff, const int8_t* lds_tile, int lds_byte) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+               :
+               : "v"(voff), "s"(ubase), "s"(lds_address(lds_tile, lds_byte))
+               : "memory", "m0");
+}
+// the same with a full 64-bit address per lane (the clamped last stage of a K that is not a multiple of the stage)
+__device__ __forceinline__ void load_lds_16_vaddr(const int8_t* vaddr, const int8_t* lds_tile, int lds_byte) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+               :
+               : "v"(vaddr), "s"(lds_address(lds_tile, lds_byte))
+               : "memory", "m0");
+}
+// A pointer that is the same for all lanes, moved to scalar registers for good.
+__device__ __forceinline__ const int8_t* uniform_pointer(const int8_t* p) {
+  const uint64_t v = (uint64_t)p;
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+  return (const int8_t*)(((uint64_t)hi << 32) | lo);
+}
+
 // Global byte offset of the chunk that belongs in LDS slot `slot_idx` of a stage starting at K offset k0.
 // Out-of-range rows / columns / K are clamped to valid addresses: what they deliver only reaches
 // outputs that are never stored (or K steps that are never run), so no zero fill is needed.
@@ -210,13 +240,20 @@ __global__ void __launch_bounds__(64 * WGM * WGN, WMIN) gemm_kernel(const GemmAr
   const int nsteps = g.K / 32;
   const int nstages = (g.K + KC - 1) / KC;
 
-  // Per-lane source pointers of stage 0 (loop invariant); a later stage adds k0 (K-major) or k0*ld (M-major).
-  const int8_t* srcA[CA];
-  const int8_t* srcB[CB];
+  // A load's address is a workgroup-uniform base (the tile's origin, advanced by k0 (K-major) or k0*ld (M-major)
+  // per stage with scalar instructions) plus a loop-invariant per-lane byte offset.  The offset fits 32 bits: a
+  // tile spans at most 256 rows (or 128 K rows) of at most 2^24 + 32 bytes.  The load takes them as scalar base
+  // + vector offset, so the K loop spends no vector ALU on addresses.
+  uint32_t offA[CA], offB[CB];
+  const int64_t originA = AK ? (int64_t)m0 * g.lda : (int64_t)m0, originB = BK ? (int64_t)n0 * g.ldb : (int64_t)n0;
 #pragma unroll
-  for (int i = 0; i < CA; ++i) srcA[i] = g.A + chunk_offset<TM, AK, KC>((i * NW + wave) * 64 + lane, m0, 0, g.M, g.K, g.lda);
+  for (int i = 0; i < CA; ++i)
+    offA[i] = (uint32_t)(chunk_offset<TM, AK, KC>((i * NW + wave) * 64 + lane, m0, 0, g.M, g.K, g.lda) - originA);
 #pragma unroll
-  for (int i = 0; i < CB; ++i) srcB[i] = g.Bm + chunk_offset<TN, BK, KC>((i * NW + wave) * 64 + lane, n0, 0, g.Nn, g.K, g.ldb);
+  for (int i = 0; i < CB; ++i)
+    offB[i] = (uint32_t)(chunk_offset<TN, BK, KC>((i * NW + wave) * 64 + lane, n0, 0, g.Nn, g.K, g.ldb) - originB);
+  const int8_t* const baseA = uniform_pointer(g.A + originA);
+  const int8_t* const baseB = uniform_pointer(g.Bm + originB);
   const int64_t kstrideA = AK ? 1 : g.lda, kstrideB = BK ? 1 : g.ldb;
   // Block scales are wave-uniform: they are read with scalar loads straight into SGPRs, ahead of their use,
   // so they cost neither LDS traffic nor vector-memory slots.  Index [a][j]: sub-tile a of the wave,
@@ -245,24 +282,23 @@ __global__ void __launch_bounds__(64 * WGM * WGN, WMIN) gemm_kernel(const GemmAr
   // known_whole: the caller guarantees k0 + KC <= K (keeps the clamping path out of the loops).
   auto issue_at = [&](int k0, int buf, auto known_whole) __attribute__((always_inline)) {
     int8_t* ta = tile_buf(buf);
-    int8_t* tb = ta + A_BYTES;
     if (known_whole || k0 + KC <= g.K) {
+      const int8_t* const sa = baseA + k0 * kstrideA;
+      const int8_t* const sb = baseB + k0 * kstrideB;
 #pragma unroll
-      for (int i = 0; i < CA; ++i)
-        __builtin_amdgcn_global_load_lds((gbl_ptr)(srcA[i] + k0 * kstrideA), (lds_ptr)(ta + 1024 * (i * NW + wave)), 16, 0, 0);
+      for (int i = 0; i < CA; ++i) load_lds_16(sa, offA[i], ta, 1024 * (i * NW + wave));
 #pragma unroll
-      for (int i = 0; i < CB; ++i)
-        __builtin_amdgcn_global_load_lds((gbl_ptr)(srcB[i] + k0 * kstrideB), (lds_ptr)(tb + 1024 * (i * NW + wave)), 16, 0, 0);
+      for (int i = 0; i < CB; ++i) load_lds_16(sb, offB[i], ta, A_BYTES + 1024 * (i * NW + wave));
     } else {  // the last stage of a K that is not a multiple of KC: clamp what lies beyond K
 #pragma unroll
       for (int i = 0; i < CA; ++i) {
         const int64_t off = chunk_offset<TM, AK, KC>((i * NW + wave) * 64 + lane, m0, k0, g.M, g.K, g.lda);
-        __builtin_amdgcn_global_load_lds((gbl_ptr)(g.A + off), (lds_ptr)(ta + 1024 * (i * NW + wave)), 16, 0, 0);
+        load_lds_16_vaddr(g.A + off, ta, 1024 * (i * NW + wave));
       }
 #pragma unroll
       for (int i = 0; i < CB; ++i) {
         const int64_t off = chunk_offset<TN, BK, KC>((i * NW + wave) * 64 + lane, n0, k0, g.Nn, g.K, g.ldb);
-        __builtin_amdgcn_global_load_lds((gbl_ptr)(g.Bm + off), (lds_ptr)(tb + 1024 * (i * NW + wave)), 16, 0, 0);
+        load_lds_16_vaddr(g.Bm + off, ta, A_BYTES + 1024 * (i * NW + wave));
       }
     }
   };

@@ -17,7 +17,8 @@
  *    lie in [-127, 127].
  *  - A scale grid is a dense row-major FP32 matrix (rows/block) x (cols/block).
  *  - `block` is the quantization block size B and must be 32, 64 or 128; every
- *    matrix dimension must be a positive multiple of it.
+ *    matrix dimension must be a positive multiple of it, at most 2^24, and a
+ *    matrix may hold at most 2^40 elements (JF_ERR_SHAPE otherwise).
  *  - All pointers must be 16-byte aligned (FP32 vectors: 4-byte) and leading
  *    dimensions multiples of 16 elements.
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).

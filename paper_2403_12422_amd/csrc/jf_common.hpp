@@ -39,8 +39,25 @@ inline int64_t ln_bwd_partial_rows(int64_t N, int64_t C, int32_t block) {
   return N / block < 512 ? N / block : 512;
 }
 inline bool valid_dim(int64_t d, int32_t block) { return d > 0 && d <= (int64_t(1) << 24) && d % block == 0; }
+// A tensor holds at most 2^40 elements (far beyond any device memory): keeps every workgroup count inside 32 bits.
+inline bool valid_size(int64_t rows, int64_t cols) { return rows * cols <= (int64_t(1) << 40); }
 
 // -------------------------------------------------------------- device side
+// The kernels that tile a matrix in two dimensions are launched as a one-dimensional grid, column group fastest:
+// the y and z dimensions of a grid stop at 65535, which a tensor of 2^24 rows exceeds.
+struct TileIndex {
+  int x, y;  // column group, row group
+};
+__device__ __forceinline__ TileIndex tile_of_workgroup(int column_groups) {
+  const unsigned i = blockIdx.x;
+  TileIndex t;
+  t.x = (int)(i % (unsigned)column_groups);
+  t.y = (int)(i / (unsigned)column_groups);
+  return t;
+}
+// host side: workgroups of such a launch
+inline unsigned tile_grid(int64_t column_groups, int64_t row_groups) { return (unsigned)(column_groups * row_groups); }
+
 // Cross-lane exchange for butterfly reductions without LDS traffic: the value of lane (id ^ 2^BIT) for every lane.
 // Bits 0..3 are DPP moves inside a row of 16 lanes (quad permutes, half-row mirror, row rotate by 8); bits 4 and 5
 // use the row / half-wave swap instructions of gfx950.  BIT 2 (half-row mirror, lane i <-> 7 - i) equals

@@ -33,6 +33,7 @@ static int32_t check_linear(const void* p0, const void* p1, const void* p2, cons
   if (!p0 || !p1 || !p2 || !p3) return JF_ERR_NULL;
   if (!valid_block(block)) return JF_ERR_BLOCK;
   if (!valid_dim(N, block) || !valid_dim(C, block) || !valid_dim(D, block)) return JF_ERR_SHAPE;
+  if (!valid_size(N, C) || !valid_size(N, D) || !valid_size(D, C)) return JF_ERR_SHAPE;
   if (!aligned16(p0) || !aligned4(p1) || !aligned16(p2) || !aligned4(p3)) return JF_ERR_ALIGN;
   return JF_OK;
 }
@@ -116,6 +117,7 @@ extern "C" int32_t jf_debug_linear_partials(int32_t which, const int8_t* A, cons
   if (which < 0 || which > 2) return JF_ERR_SHAPE;
   if (!valid_block(block)) return JF_ERR_BLOCK;
   if (!valid_dim(N, block) || !valid_dim(C, block) || !valid_dim(D, block)) return JF_ERR_SHAPE;
+  if (!valid_size(N, C) || !valid_size(N, D) || !valid_size(D, C)) return JF_ERR_SHAPE;
   if (!aligned16(A) || !aligned16(Bm) || !aligned16(out)) return JF_ERR_ALIGN;
   const int64_t K = which == 0 ? C : (which == 1 ? D : N);
   if (kb < 0 || kb >= K / block) return JF_ERR_SHAPE;

@@ -105,9 +105,10 @@ __global__ void __launch_bounds__(256) gelu_kernel(const int8_t* __restrict__ X,
   __shared__ float s_amax[4][4 * J];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int ch = lane & 7, rsub = lane >> 3;
-  const int c0 = blockIdx.x * (128 * J);
-  const int r0 = blockIdx.y * B + wave * (B / 4);
-  const int lc = cols / B, bi = blockIdx.y;
+  const TileIndex wg = tile_of_workgroup((cols + 128 * J - 1) / (128 * J));
+  const int c0 = wg.x * (128 * J);
+  const int r0 = wg.y * B + wave * (B / 4);
+  const int lc = cols / B, bi = wg.y;
   int col[J];
   bool col_ok[J];  // cols % 32 == 0 and chunks are 16 wide: a 32-column group is all in or all out
 #pragma unroll
@@ -228,10 +229,11 @@ __global__ void __launch_bounds__(256) add_kernel(const int8_t* __restrict__ X1,
   __shared__ float s_amax[4][4];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int ch = lane & 7, rsub = lane >> 3;
-  const int col = blockIdx.x * 128 + 16 * ch;
-  const int r0 = blockIdx.y * B + wave * (B / 4);
+  const TileIndex wg = tile_of_workgroup((cols + 127) / 128);
+  const int col = wg.x * 128 + 16 * ch;
+  const int r0 = wg.y * B + wave * (B / 4);
   const bool col_ok = col < cols;
-  const int lc = cols / B, bi = blockIdx.y;
+  const int lc = cols / B, bi = wg.y;
 
   float y[P][16];
   float m = 0.0f;
@@ -290,10 +292,11 @@ __global__ void __launch_bounds__(256) dropout_kernel(const int8_t* __restrict__
   __shared__ float s_amax[4][4];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int ch = lane & 7, rsub = lane >> 3;
-  const int col = blockIdx.x * 128 + 16 * ch;
-  const int r0 = blockIdx.y * B + wave * (B / 4);
+  const TileIndex wg = tile_of_workgroup((cols + 127) / 128);
+  const int col = wg.x * 128 + 16 * ch;
+  const int r0 = wg.y * B + wave * (B / 4);
   const bool col_ok = col < cols;
-  const int lc = cols / B, bi = blockIdx.y;
+  const int lc = cols / B, bi = wg.y;
 
   float y[P][16];
   float m = 0.0f;
@@ -939,8 +942,8 @@ __global__ void __launch_bounds__(1024) colsum_kernel(const float* __restrict__ 
 template <bool BWD, int B, int J>
 static void launch_gelu_cfg(const int8_t* X, const float* SX, const int8_t* G, const float* SG, int rows, int cols,
                             int8_t* Y, float* SY, hipStream_t st) {
-  hipLaunchKernelGGL((gelu_kernel<BWD, B, J>), dim3((cols + 128 * J - 1) / (128 * J), rows / B), dim3(256), 0, st, X, SX, G,
-                     SG, rows, cols, Y, SY);
+  hipLaunchKernelGGL((gelu_kernel<BWD, B, J>), dim3(tile_grid((cols + 128 * J - 1) / (128 * J), rows / B)), dim3(256), 0, st,
+                     X, SX, G, SG, rows, cols, Y, SY);
 }
 template <bool BWD>
 static void launch_gelu(int block, const int8_t* X, const float* SX, const int8_t* G, const float* SG, int rows,
@@ -963,7 +966,7 @@ static int32_t check_eltwise(const void* x, const void* sx, const void* y, const
                              int32_t block) {
   if (!x || !sx || !y || !sy) return JF_ERR_NULL;
   if (!valid_block(block)) return JF_ERR_BLOCK;
-  if (!valid_dim(N, block) || !valid_dim(C, block)) return JF_ERR_SHAPE;
+  if (!valid_dim(N, block) || !valid_dim(C, block) || !valid_size(N, C)) return JF_ERR_SHAPE;
   if (!aligned16(x) || !aligned4(sx) || !aligned16(y) || !aligned4(sy)) return JF_ERR_ALIGN;
   return JF_OK;
 }
@@ -1062,7 +1065,7 @@ extern "C" int32_t jf_dropout_q(const int8_t* X, const float* SX, const uint8_t*
   if (!(p >= 0.0f && p < 1.0f)) return JF_ERR_SHAPE;
   if (reinterpret_cast<uintptr_t>(mask_bits) & 1u) return JF_ERR_ALIGN;
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-  const dim3 grid((unsigned)((C + 127) / 128), (unsigned)(N / block));
+  const dim3 grid(tile_grid((C + 127) / 128, N / block));
   const float keep_scale = (float)(1.0 / (1.0 - (double)p));
   const int rows = (int)N, cols = (int)C;
   if (block == 32) hipLaunchKernelGGL((dropout_kernel<32>), grid, dim3(256), 0, st, X, SX, mask_bits, keep_scale, rows, cols, Y, SY);
@@ -1080,7 +1083,7 @@ extern "C" int32_t jf_add_q(const int8_t* X1, const float* S1, const int8_t* X2,
   if ((row_mean == nullptr) != (row_sumsq == nullptr)) return JF_ERR_NULL;
   if (!aligned16(X2) || !aligned4(S2) || (row_mean && (!aligned4(row_mean) || !aligned4(row_sumsq)))) return JF_ERR_ALIGN;
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-  const dim3 grid((unsigned)((C + 127) / 128), (unsigned)(N / block));
+  const dim3 grid(tile_grid((C + 127) / 128, N / block));
   const int rows = (int)N, cols = (int)C;
   if (block == 32) hipLaunchKernelGGL((add_kernel<32>), grid, dim3(256), 0, st, X1, S1, X2, S2, rows, cols, Y, SY, row_mean, row_sumsq);
   else if (block == 64) hipLaunchKernelGGL((add_kernel<64>), grid, dim3(256), 0, st, X1, S1, X2, S2, rows, cols, Y, SY, row_mean, row_sumsq);

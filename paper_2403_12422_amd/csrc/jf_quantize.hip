@@ -34,8 +34,9 @@ __global__ void __launch_bounds__(256) quantize_kernel(const T* __restrict__ x, 
   __shared__ float s_amax[4][4];                       // [32-row strip][32-col group]
   __shared__ __align__(16) uint8_t s_codes[TRANSPOSED_COPY ? 128 * 132 : 16];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int r0 = blockIdx.y * 128 + wave * 32;        // first row of this wave's strip
-  const int c0 = blockIdx.x * 128;
+  const TileIndex wg = tile_of_workgroup((cols + 127) / 128);
+  const int r0 = wg.y * 128 + wave * 32;               // first row of this wave's strip
+  const int c0 = wg.x * 128;
   const int c4 = lane & 31, rh = lane >> 5;
   const int col = c0 + 4 * c4;
   const bool col_ok = col < cols;                      // cols % 32 == 0: whole 8-lane groups are in or out
@@ -87,7 +88,7 @@ __global__ void __launch_bounds__(256) quantize_kernel(const T* __restrict__ x, 
     // thread -> (tile column tc, 16-row chunk ch): gathers a column run and writes 16 bytes of qT
     for (int e = threadIdx.x; e < 128 * 8; e += 256) {
       const int tc = e >> 3, ch = e & 7;
-      const int gc = c0 + tc, gr = blockIdx.y * 128 + 16 * ch;
+      const int gc = c0 + tc, gr = wg.y * 128 + 16 * ch;
       if (gc < cols && gr < rows) {  // rows % 32 == 0: a 16-row chunk is entirely in or out
         uint32_t w[4];
 #pragma unroll
@@ -106,7 +107,7 @@ __global__ void __launch_bounds__(256) quantize_kernel(const T* __restrict__ x, 
 template <typename T, int B>
 static void launch_quantize(const T* x, int64_t ldx, int rows, int cols, int8_t* q, int64_t ldq, float* s, int8_t* qT,
                             int64_t ldqT, float* sT, hipStream_t st) {
-  dim3 grid((cols + 127) / 128, (rows + 127) / 128);
+  dim3 grid(tile_grid((cols + 127) / 128, (rows + 127) / 128));
   if (qT)
     hipLaunchKernelGGL((quantize_kernel<T, B, true>), grid, dim3(256), 0, st, x, ldx, rows, cols, q, ldq, s, qT, ldqT, sT);
   else
@@ -164,7 +165,7 @@ extern "C" int32_t jf_dequantize_block(const int8_t* q, const float* s, int64_t 
   if (!q || !s || !out) return JF_ERR_NULL;
   if (out_dtype != 0 && out_dtype != 1) return JF_ERR_DTYPE;
   if (!valid_block(block)) return JF_ERR_BLOCK;
-  if (!valid_dim(rows, block) || !valid_dim(cols, block) || ldo < cols) return JF_ERR_SHAPE;
+  if (!valid_dim(rows, block) || !valid_dim(cols, block) || !valid_size(rows, cols) || ldo < cols) return JF_ERR_SHAPE;
   if (!aligned16(q) || !aligned4(s) || !aligned16(out) || (ldo % 8)) return JF_ERR_ALIGN;
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   const int64_t total = rows * (cols / 16);
@@ -186,7 +187,7 @@ extern "C" int32_t jf_quantize_block(const void* x, int32_t x_dtype, int64_t row
   if ((qT == nullptr) != (sT == nullptr)) return JF_ERR_NULL;
   if (x_dtype != 0 && x_dtype != 1) return JF_ERR_DTYPE;
   if (!valid_block(block)) return JF_ERR_BLOCK;
-  if (!valid_dim(rows, block) || !valid_dim(cols, block)) return JF_ERR_SHAPE;
+  if (!valid_dim(rows, block) || !valid_dim(cols, block) || !valid_size(rows, cols)) return JF_ERR_SHAPE;
   if (ldx < cols || ldq < cols || (qT && ldqT < rows)) return JF_ERR_SHAPE;
   if (!aligned16(x) || !aligned16(q) || !aligned4(s) || (ldx % 16) || (ldq % 16)) return JF_ERR_ALIGN;
   if (qT && (!aligned16(qT) || !aligned4(sT) || (ldqT % 16))) return JF_ERR_ALIGN;

@@ -49,6 +49,7 @@ def test_argument_validation_returns_codes_without_launching():
     assert lin(N=0) == 2                                   # JF_ERR_SHAPE: empty
     assert lin(N=48) == 2                                  # not a multiple of block
     assert lin(C=(1 << 24) + 32) == 2                      # above the supported maximum
+    assert lin(N=1 << 24, C=1 << 24) == 2                  # more than 2^40 elements in one matrix
     assert lin(block=48) == 3                              # JF_ERR_BLOCK
     assert lin(X=ODD) == 4                                 # JF_ERR_ALIGN
     # wgrad needs at least one output, and codes/scales come together
@@ -65,6 +66,7 @@ def test_argument_validation_returns_codes_without_launching():
     assert qz(qT=FAKE) == 1                                # qT without sT
     # element-wise ops and the LayerNorm-backward workspace
     assert lib.jf_gelu_q(FAKE, FAKE, 64, 65, 32, FAKE, FAKE, None) == 2
+    assert lib.jf_gelu_q(FAKE, FAKE, 1 << 24, 1 << 24, 32, FAKE, FAKE, None) == 2
     assert lib.jf_gelu_q_bwd(None, FAKE, FAKE, FAKE, 64, 64, 32, FAKE, FAKE, None) == 1
     assert lib.jf_layernorm_q(FAKE, FAKE, None, FAKE, ctypes.c_float(1e-5), 64, 64, 32, FAKE, FAKE, FAKE, FAKE, None) == 1
     assert lib.jf_layernorm_q_bwd(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 64, 64, 32, FAKE, FAKE, FAKE, FAKE, FAKE, 16, None) == 5

@@ -53,6 +53,59 @@ def test_random_shapes_every_operator(case):
     np.testing.assert_array_equal(host(jf.jf_dequantize_block(Xd, SXd, block)), oracle.dequantize(X, SX, block).astype(np.float32))
 
 
+def _bands(rows, block, unit):
+    """Row ranges at the top, around row group 65535 (where a grid's y dimension would end) and at the bottom;
+    unit = rows per workgroup of the kernel under test."""
+    edge = 65535 * unit
+    return [(0, 2 * block), (edge - 2 * block, edge + 2 * block), (rows - 2 * block, rows)]
+
+
+@pytest.mark.parametrize("block", [32, 128])
+def test_more_row_groups_than_a_grid_dimension_holds(block):
+    """Tall tensors: more row groups than the 65535 a grid's y or z dimension can hold (the kernels number their
+    workgroups along x).  The tensors are drawn on the GPU; bands of whole block rows -- the operators work block
+    by block -- are checked against the oracle."""
+    say(f"tall tensors, block {block}")
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(240312422 + block)
+    rnd = lambda shape, sd: torch.randn(shape, generator=gen, device="cuda:0", dtype=torch.float32) * sd
+
+    # quantizer: workgroups of 128 rows
+    rows, cols = 128 * 65536 + 256, block
+    x = rnd((rows, cols), 1.0)
+    q, s = jf.jf_quantize_block(x, block)
+    for r0, r1 in _bands(rows, block, 128):
+        oq, os_ = oracle.quantize_block(host(x[r0:r1]), block)
+        np.testing.assert_array_equal(host(q[r0:r1]), oq)
+        np.testing.assert_array_equal(host(s[r0 // block:r1 // block]), os_)
+    np.testing.assert_array_equal(host(jf.jf_dequantize_block(q, s, block)[rows - block:]),
+                                  oracle.dequantize(host(q[rows - block:]), host(s[-1:]), block).astype(np.float32))
+    del x, q, s
+
+    # element-wise operators: workgroups of `block` rows
+    rows, cols = block * 65536 + 2 * block, 2 * block
+    codes = lambda: torch.randint(-127, 128, (rows, cols), generator=gen, device="cuda:0", dtype=torch.int8)
+    scales = lambda sd: (torch.rand((rows // block, cols // block), generator=gen, device="cuda:0") + 0.5) * sd
+    X, SX, G, SG = codes(), scales(0.02), codes(), scales(1e-5)
+    bits = torch.randint(0, 256, (rows, cols // 8), generator=gen, device="cuda:0", dtype=torch.uint8)
+    gamma, beta = 1.0 + rnd((cols,), 0.1), rnd((cols,), 0.1)
+    got = {"gelu": jf.jf_gelu_q(X, SX, block), "gelu bwd": jf.jf_gelu_q_bwd(G, SG, X, SX, block),
+           "add": jf.jf_add_q(X, SX, G, SG, block)[:2], "dropout": jf.jf_dropout_q(X, SX, bits, 0.25, block)}
+    ln = jf.jf_layernorm_q(X, SX, gamma, beta, 1e-5, block)
+    for r0, r1 in _bands(rows, block, block):
+        b0, b1 = r0 // block, r1 // block
+        Xh, SXh, Gh, SGh = host(X[r0:r1]), host(SX[b0:b1]), host(G[r0:r1]), host(SG[b0:b1])
+        want = {"gelu": oracle.gelu_q(Xh, SXh, block), "gelu bwd": oracle.gelu_q_bwd(Gh, SGh, Xh, SXh, block),
+                "dropout": oracle.dropout_q(Xh, SXh, host(bits[r0:r1]), 0.25, block)}
+        o = oracle.add_q(Xh, SXh, Gh, SGh, block)
+        want["add"] = (o[0], o[1], o[4])
+        for name, (oq, os_, of) in want.items():
+            _check_eltwise(f"{name} rows {r0}..{r1}", got[name][0][r0:r1], got[name][1][b0:b1], oq, os_, of, block)
+        oY, oSY, omean, orstd, of = oracle.layernorm_q(Xh, SXh, host(gamma), host(beta), 1e-5, block)
+        _check_eltwise(f"layernorm rows {r0}..{r1}", ln[0][r0:r1], ln[1][b0:b1], oY, oSY, of, block)
+        np.testing.assert_allclose(host(ln[3][r0:r1]), orstd, rtol=1e-5)
+
+
 def test_hot_path_replayed_from_a_hip_graph():
     """The whole step (quantize, LayerNorm, the three products, GELU forward / backward, LayerNorm backward) captured
     once and replayed: every replay must reproduce the eager results bit for bit, with eager work and

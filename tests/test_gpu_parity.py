@@ -258,6 +258,18 @@ def _check_sampled(name, got, A, SA, Bm, SB, block, g, nblk=48):
     say(f"  {name}: {len(bp)} sampled blocks ok, {nbad} tie codes")
 
 
+def test_linear_output_past_2_31_elements():
+    """A forward product whose output has more than 2^31 elements (65536 x 32800, K = 64): the epilogue's
+    addresses need 64 bits.  Sampled blocks and row bands, as for the large-GEMM sweep."""
+    block, N, C, D = 32, 65536, 64, 32800
+    say(f"linear fwd with a {N} x {D} output")
+    g = workloads.rng(5300)
+    (X, SX), (W, SW) = (oracle.quantize_block(workloads.gaussian(g, r, C, 1.0), block) for r in (N, D))
+    got = jf.jf_linear_fwd(dev(X), dev(SX), dev(W), dev(SW), block, want_f32=True)
+    assert got[0].numel() > (1 << 31)
+    _check_sampled("fwd", got, X, SX, W, SW, block, g, 32)
+
+
 def test_linear_config2_full_size_sampled():
     """GPT-2-small MLP shape (tokens 4096, in 768, out 3072, block 32) in the launch configuration the benchmark times."""
     block, N, C, D = 32, 4096, 768, 3072

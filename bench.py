@@ -435,6 +435,9 @@ def main():
     ops["add_with_row_partials"] = (lambda: jf.jf_add_q(Y, SY, H, SH, B, want_partials=True, out=(dY, SdY, rm, rq)),
                                     N * D * (3 + 3 * sb + 8.0 / B))
     ops["dropout"] = (lambda: jf.jf_dropout_q(Y, SY, mask_bits, 0.1, B, out=(dY, SdY)), N * D * (2.125 + 2 * sb))
+    # the hand-over to a floating-point operator (the FP16 attention core): INT8 -> FP16
+    h16 = torch.empty((N, D), dtype=torch.float16, device=dev)
+    ops["dequantize_f16"] = (lambda: jf.jf_dequantize_block(Y, SY, B, dtype=torch.float16, out=h16), N * D * (3 + sb))
     memops = {}
     for name, (fn, nbytes) in ops.items():
         ms = op_ms(fn)
@@ -458,11 +461,16 @@ def main():
             "gelu_fwd": (lambda: jf.jf_gelu_q(xg, sxg, B, out=(yg, syg)), NG * D * (2 + 2 * sb)),
             "gelu_bwd": (lambda: jf.jf_gelu_q_bwd(gg, sgg, xg, sxg, B, out=(yg, syg)), NG * D * (3 + 3 * sb)),
         }
+        big["add"] = (lambda: jf.jf_add_q(xg, sxg, gg, sgg, B, out=(yg, syg)), NG * D * (3 + 3 * sb))
+        mbg = torch.randint(0, 256, (NG, D // 8), generator=gen, dtype=torch.uint8, device=dev)
+        big["dropout"] = (lambda: jf.jf_dropout_q(xg, sxg, mbg, 0.1, B, out=(yg, syg)), NG * D * (2.125 + 2 * sb))
+        # what a plain device-to-device copy of the same tensor reaches (torch's copy kernel): the practical HBM rate
+        big["plain_copy_reference"] = (lambda: yg.copy_(xg), NG * D * 2)
         for name, (fn, nbytes) in big.items():
             ms = op_ms(fn, reps=4, replays=3)
             memops_hbm[name] = {"tokens": NG, "ms": round(ms, 4), "GB/s": round(nbytes / (ms * 1e-3) * 1e-9, 1),
                                 "frac_hbm_peak": round(nbytes / (ms * 1e-3) * 1e-9 / HBM_PEAK_GBPS, 4)}
-        del xg, sxg, gg, sgg, yg, syg
+        del xg, sxg, gg, sgg, yg, syg, mbg
         torch.cuda.empty_cache()
         xl, sxl, gl, sgl = ri8(NL, C), rsc(NL, C, 0.05), ri8(NL, C), rsc(NL, C, 3e-5)
         yl, syl, ml, rl = i8(NL, C), sc(NL, C), f32(NL), f32(NL)

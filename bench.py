@@ -391,6 +391,9 @@ def main():
     gemm_ms = [e0.elapsed_time(e1) for e0, e1 in gemm_events]
     gemm_avg_ms = sum(gemm_ms) / len(gemm_ms)
     per_gemm = [sum(gemm_ms[i::3]) / len(gemm_ms[i::3]) for i in range(3)]
+    median = lambda v: sorted(v)[len(v) // 2]
+    per_gemm_median = [median(gemm_ms[i::3]) for i in range(3)]
+    per_gemm_min = [min(gemm_ms[i::3]) for i in range(3)]
     gemm_ops = 2.0 * N * C * D
     achieved = gemm_ops / (gemm_avg_ms * 1e-3) * 1e-12
 
@@ -532,6 +535,9 @@ def main():
                             "algorithmic bytes are 18.1e6",
             "avg_launch_ms": round(gemm_avg_ms, 5),
             "per_launch_ms": {"fwd": round(per_gemm[0], 5), "dgrad": round(per_gemm[1], 5), "wgrad": round(per_gemm[2], 5)},
+            "per_launch_ms_median": dict(zip(("fwd", "dgrad", "wgrad"), (round(v, 5) for v in per_gemm_median))),
+            "per_launch_ms_min": dict(zip(("fwd", "dgrad", "wgrad"), (round(v, 5) for v in per_gemm_min))),
+            "launches_timed": len(gemm_ms),
             "linear_only_TOPS": round(6.0 * N * C * D / (sum(per_gemm) * 1e-3) * 1e-12, 2),
         },
         "memory_bound_ops": memops,

@@ -186,7 +186,8 @@ __device__ __forceinline__ void fold(float (&acc)[16], const v16i& v, float t) {
 }
 
 // WMIN = minimum resident waves per SIMD the register allocation must allow.
-template <int B, int WM, int WN, int WGM, int WGN, bool AK, bool BK, bool DUMP, int WMIN>
+// DEEP: a stage of 128 K bytes where the shape's default is 64.
+template <int B, int WM, int WN, int WGM, int WGN, bool AK, bool BK, bool DUMP, int WMIN, bool DEEP = false>
 __global__ void __launch_bounds__(64 * WGM * WGN, WMIN) gemm_kernel(const GemmArgs g) {
   constexpr int NW = WGM * WGN;
   constexpr int TM = 32 * WM * WGM, TN = 32 * WN * WGN;
@@ -196,7 +197,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN, WMIN) gemm_kernel(const GemmAr
   // expensive), and for the one-sub-block waves at B = 64 (a stage must hold an even number of sub-block x
   // K-block units); 64 otherwise, which lets three workgroups with a ring of three stages share the LDS of a
   // compute unit.
-  constexpr int KC = (B == 128 || (WGM * WGN > 4 && WM * WN < 4) || (B == 64 && WM * WN == 1)) ? 128 : 64;
+  constexpr int KC = (DEEP || B == 128 || (WGM * WGN > 4 && WM * WN < 4) || (B == 64 && WM * WN == 1)) ? 128 : 64;
   constexpr int SPS = KC / 32;  // MFMA K steps per stage
   constexpr int NTILE = WM * WN;
   typedef TileLayout<TM, AK, KC> LA;
@@ -625,15 +626,16 @@ __global__ void __launch_bounds__(64 * WGM * WGN, WMIN) gemm_kernel(const GemmAr
 }
 
 // --------------------------------------------------------------------- host
-template <int B, int WM, int WN, int WGM, int WGN, bool AK, bool BK, bool DUMP>
+template <int B, int WM, int WN, int WGM, int WGN, bool AK, bool BK, bool DUMP, bool DEEP = false>
 static void launch_cfg(const GemmArgs& a, hipStream_t st) {
   constexpr int TM = 32 * WM * WGM, TN = 32 * WN * WGN;
   // resident waves per SIMD the register allocation has to allow: 3 for the 2x2 wave tile (three
   // 128x128 workgroups share a compute unit), the waves of the one workgroup per compute unit for the big
   // workgroups (2 for eight waves, 3 for nine or twelve), 4 for the 64x64 tiles
-  constexpr int WMIN = (WM * WN >= 4 && WGM * WGN == 8) ? 2 : (WM * WN >= 4) ? 3 : (WGM * WGN > 8 ? 3 : (WGM * WGN > 4 ? 2 : 4));
+  // (3 for the 64x64 tiles with a stage of 128 K bytes: their ring leaves room for three workgroups per compute unit)
+  constexpr int WMIN = (WM * WN >= 4 && WGM * WGN == 8) ? 2 : (WM * WN >= 4) ? 3 : (WGM * WGN > 8 ? 3 : (WGM * WGN > 4 ? 2 : ((DEEP || B == 64) ? 3 : 4)));
   const int tiles = ((a.M + TM - 1) / TM) * ((a.Nn + TN - 1) / TN);
-  hipLaunchKernelGGL((gemm_kernel<B, WM, WN, WGM, WGN, AK, BK, DUMP, WMIN>), dim3(tiles), dim3(64 * WGM * WGN), 0, st, a);
+  hipLaunchKernelGGL((gemm_kernel<B, WM, WN, WGM, WGN, AK, BK, DUMP, WMIN, DEEP>), dim3(tiles), dim3(64 * WGM * WGN), 0, st, a);
 }
 
 // Tile shapes.  At B = 32 the kernel is bound by the vector ALU work of the per-K-block dequantization, which
@@ -643,7 +645,9 @@ static void launch_cfg(const GemmArgs& a, hipStream_t st) {
 //   128x128  four waves of 2x2 sub-blocks, three workgroups per compute unit;
 //   128x96   twelve waves of one sub-block } one workgroup per compute unit, for outputs with too few
 //    96x96   nine waves of one sub-block   } 128x128 tiles to fill 256 compute units evenly;
-//    64x64   four waves of one sub-block.
+//    64x64   four waves of one sub-block; with a stage of 128 K bytes (half the barriers, 9 % faster in the K loop,
+//            but only three instead of four workgroups fit a compute unit) when the output has at most 768 such
+//            tiles and one operand is K-major.
 extern int g_forced_shape;  // test hook, see jf_debug_set_gemm_shape
 struct ShapeCost {
   int64_t cycles;
@@ -687,12 +691,17 @@ static void launch_shape(const GemmArgs& a, hipStream_t st) {
       c128 = g_forced_shape == 1 ? 0 : big;
       c12896 = g_forced_shape == 2 ? 0 : big;
       c9696 = g_forced_shape == 3 ? 0 : big;
-      c64 = g_forced_shape == 4 ? 0 : big;
+      c64 = (g_forced_shape == 4 || g_forced_shape == 7) ? 0 : big;
     }
     if (c128 <= c12896 && c128 <= c9696 && c128 <= c64) launch_cfg<B, 2, 2, 2, 2, AK, BK, DUMP>(a, st);
     else if (c12896 <= c9696 && c12896 <= c64) launch_cfg<B, 1, 1, 4, 3, AK, BK, DUMP>(a, st);
     else if (c9696 <= c64) launch_cfg<B, 1, 1, 3, 3, AK, BK, DUMP>(a, st);
-    else launch_cfg<B, 1, 1, 2, 2, AK, BK, DUMP>(a, st);
+    else {
+      const int64_t n64 = (int64_t)((a.M + 63) / 64) * ((a.Nn + 63) / 64);
+      const bool deep = g_forced_shape ? g_forced_shape == 7 : ((AK || BK) && n64 <= 768);
+      if (deep) launch_cfg<B, 1, 1, 2, 2, AK, BK, DUMP, true>(a, st);
+      else launch_cfg<B, 1, 1, 2, 2, AK, BK, DUMP>(a, st);
+    }
   }
 }
 

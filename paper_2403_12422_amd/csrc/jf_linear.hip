@@ -129,7 +129,7 @@ extern "C" int32_t jf_debug_linear_partials(int32_t which, const int8_t* A, cons
 }
 
 extern "C" int32_t jf_debug_set_gemm_shape(int32_t shape) {
-  if (shape < 0 || shape > 6 || shape == 5) return JF_ERR_SHAPE;
+  if (shape < 0 || shape > 7 || shape == 5) return JF_ERR_SHAPE;
   jf::g_forced_shape = shape;
   return JF_OK;
 }

@@ -2,7 +2,8 @@
 
 They measure the machine limits that the GEMM design is judged against: the issue rate of the dequantize fold next
 to INT8 MFMAs (``fold_issue_rate``, and with real data dependences ``fold_chain_rate``), what the LDS fragment
-reads, the stage barrier and the direct-to-LDS loads of the real K loop add to it (``kloop_overheads``), and the L2 /
+reads, the stage barrier and the direct-to-LDS loads of the real K loop add to it (``kloop_overheads``), a model of the
+whole K loop per tile shape and block size (``kloop_model``), and the L2 /
 last-level-cache bandwidth a compute unit sees (``l2_bandwidth``).
 """
 import os
@@ -15,7 +16,7 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-Xclang", "-target-feature", "-Xclang"
 
 def main(names):
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    for name in names or ["fold_issue_rate", "fold_chain_rate", "kloop_overheads", "l2_bandwidth"]:
+    for name in names or ["fold_issue_rate", "fold_chain_rate", "kloop_overheads", "kloop_model", "l2_bandwidth"]:
         src, exe = os.path.join(HERE, name + ".hip"), os.path.join(HERE, "_build_" + name)
         res = subprocess.run([hipcc, *FLAGS, src, "-o", exe], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
         if res.returncode != 0:

@@ -538,6 +538,12 @@ def main():
             "per_launch_ms_median": dict(zip(("fwd", "dgrad", "wgrad"), (round(v, 5) for v in per_gemm_median))),
             "per_launch_ms_min": dict(zip(("fwd", "dgrad", "wgrad"), (round(v, 5) for v in per_gemm_min))),
             "launches_timed": len(gemm_ms),
+            # second ceiling of this method on this chip (block 32): the per-K-block dequantize fold issues 32 vector
+            # instructions per MFMA; measured with no memory traffic (fold_chain_rate) and with the LDS reads, barrier
+            # and direct-to-LDS loads of a real K loop (kloop_overheads), see the profile named below
+            "valu_fold_ceiling": {"bare_TOPS": 1461.0, "with_k_loop_overheads_TOPS": 1194.0,
+                                  "frac_of_bare": round(achieved / 1461.0, 4),
+                                  "source": "profiles/microbench_fold_issue_rate_and_l2_bandwidth.txt"} if B == 32 else None,
             "linear_only_TOPS": round(6.0 * N * C * D / (sum(per_gemm) * 1e-3) * 1e-12, 2),
         },
         "memory_bound_ops": memops,

@@ -136,11 +136,15 @@ __global__ void __launch_bounds__(256) gelu_kernel(const int8_t* __restrict__ X,
   // per table.  Entry 128 (code -128, which no quantizer output holds) is set to 0.
   {
     const int i = threadIdx.x & 127;
+    // the table index is the same for all lanes of a wave, so the block scale comes through the scalar cache
+    // (constant address space: the grid is never written by this kernel)
+    typedef const __attribute__((address_space(4))) float* const_f32_ptr;
+    const const_f32_ptr sx_row = (const_f32_ptr)SX + (int64_t)bi * lc;
 #pragma unroll
-    for (int k = threadIdx.x >> 7; k < NTAB; k += 2) {
+    for (int k = __builtin_amdgcn_readfirstlane(threadIdx.x >> 7); k < NTAB; k += 2) {
       const int bcol = c0 + (k / TPH) * 128 + (k % TPH) * B;
       if (bcol < cols) {
-        const float a = (float)i * SX[(int64_t)bi * lc + bcol / B];
+        const float a = (float)i * sx_row[bcol / B];
         const TailEval te = normal_tail(a);
         float pos, neg;  // f(+a), f(-a)
         if (BWD) {       // x phi(x) + Phi(x)

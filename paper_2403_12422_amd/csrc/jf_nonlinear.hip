@@ -93,7 +93,7 @@ __device__ __forceinline__ float strip_block_max(float m) {
 // GELU forward / backward.  One workgroup of four waves owns B rows x J*128 columns = J*128/min(B,128)
 // quantization blocks; wave w owns rows [w*B/4, (w+1)*B/4) in B/32 passes of 8 rows, lane = (row l/8,
 // 16-byte chunk l%8) in each of the J 128-column halves, so every row segment is a full 128-byte line.
-// J = 2 halves the number of workgroups, tables built per element stay the same; the host picks J by size.
+// J = 2 (B = 32, 64) halves the number of workgroups; the tables built per element stay the same.
 template <bool BWD, int B, int J>
 __global__ void __launch_bounds__(256) gelu_kernel(const int8_t* __restrict__ X, const float* __restrict__ SX,
                                                     const int8_t* __restrict__ G, const float* __restrict__ SG,
@@ -217,6 +217,101 @@ __global__ void __launch_bounds__(256) gelu_kernel(const int8_t* __restrict__ X,
       *reinterpret_cast<uint4*>(Y + (int64_t)row * cols + col[j]) = quantize16(y[j][p], inv);
     }
   }
+}
+
+// GELU forward / backward for B = 32 and 64 with one quantization block per WAVE: the wave builds the block's
+// table, looks its B x B codes up, takes the block max-abs with a wave reduction and stores -- no workgroup
+// barrier and no LDS exchange between waves, so the four waves of a workgroup (four neighbouring block columns)
+// run independently and one wave's table build overlaps its neighbours' loads and stores.  Lane = (row l / CPR,
+// 16-byte chunk l % CPR) with CPR = B/16 chunks per block row, in B*CPR/64 passes; the four waves of a workgroup
+// read neighbouring 32- or 64-byte pieces of the same memory lines.
+template <bool BWD, int B>
+__global__ void __launch_bounds__(256) gelu_wave_kernel(const int8_t* __restrict__ X, const float* __restrict__ SX,
+                                                         const int8_t* __restrict__ G, const float* __restrict__ SG,
+                                                         int rows, int cols, int8_t* __restrict__ Y, float* __restrict__ SY) {
+  constexpr int CPR = B / 16, RPP = 64 / CPR, P = B / RPP;  // chunks per block row, rows per pass, passes
+  __shared__ float s_tab[4][256];  // one table per wave, indexed by the code byte taken as unsigned
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int lc = cols / B;
+  const TileIndex wg = tile_of_workgroup((lc + 3) / 4);
+  const int bi = wg.y, bj = wg.x * 4 + wave;
+  if (bj >= lc) return;  // wave-uniform; the kernel has no workgroup barrier
+  const int ch = lane % CPR, rsub = lane / CPR;
+  const int64_t base = (int64_t)(bi * B + rsub) * cols + bj * B + 16 * ch;
+
+  // codes first: their latency runs beside the table build
+  uint4 px[P], pg[BWD ? P : 1];
+#pragma unroll
+  for (int p = 0; p < P; ++p) {
+    px[p] = *reinterpret_cast<const uint4*>(X + base + (int64_t)p * RPP * cols);
+    if (BWD) pg[p] = *reinterpret_cast<const uint4*>(G + base + (int64_t)p * RPP * cols);
+  }
+
+  // the block's table: 128 tail evaluations, two per lane (see gelu_kernel); scales through the scalar cache
+  typedef const __attribute__((address_space(4))) float* const_f32_ptr;
+  const float sx = ((const_f32_ptr)SX)[(int64_t)bi * lc + bj];
+  float* tab = s_tab[wave];
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const int i = lane + 64 * h;
+    const float a = (float)i * sx;
+    const TailEval te = normal_tail(a);
+    float pos, neg;
+    if (BWD) {
+      const float slope = a * 0.39894228040143268f;
+      pos = __builtin_fmaf(slope, te.ez, 1.0f - te.q);
+      neg = __builtin_fmaf(-slope, te.ez, te.q);
+    } else {
+      const float aq = a * te.q;
+      pos = a - aq;
+      neg = 0.0f - aq;
+    }
+    tab[i] = pos;
+    tab[i == 0 ? 128 : 256 - i] = i == 0 ? 0.0f : neg;
+  }
+  // The table is written and read by this wave only; LDS serves a wave's accesses in program order, and the
+  // fence keeps the compiler from moving the lookups above the writes.
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+  float sg = 0.0f, sg128 = 0.0f;
+  if (BWD) {
+    sg = ((const_f32_ptr)SG)[(int64_t)bi * lc + bj];
+    sg128 = -128.0f * sg;
+  }
+  float y[P][16];
+  float m = 0.0f;
+#pragma unroll
+  for (int p = 0; p < P; ++p) {
+    const uint32_t w[4] = {px[p].x, px[p].y, px[p].z, px[p].w};
+    float f[16];
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+      f[4 * d + 0] = tab[w[d] & 0xffu];
+      f[4 * d + 1] = tab[(w[d] >> 8) & 0xffu];
+      f[4 * d + 2] = tab[(w[d] >> 16) & 0xffu];
+      f[4 * d + 3] = tab[w[d] >> 24];
+    }
+    if (BWD) {
+      float ug[16];
+      unpack16_biased(pg[p], ug);
+#pragma unroll
+      for (int e = 0; e < 16; ++e) y[p][e] = __builtin_fmaf(ug[e], sg, sg128) * f[e];
+    } else {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) y[p][e] = f[e];
+    }
+#pragma unroll
+    for (int e = 0; e < 16; e += 4) m = amax4(m, y[p][e], y[p][e + 1], y[p][e + 2], y[p][e + 3]);
+  }
+  m = wave_group_max<63>(m);
+  float scale, inv;
+  block_scale(m, scale, inv);
+  if (lane == 0) SY[(int64_t)bi * lc + bj] = scale;
+#pragma unroll
+  for (int p = 0; p < P; ++p) *reinterpret_cast<uint4*>(Y + base + (int64_t)p * RPP * cols) = quantize16(y[p], inv);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -943,6 +1038,12 @@ __global__ void __launch_bounds__(1024) colsum_kernel(const float* __restrict__ 
 }
 
 // ------------------------------------------------------------------------------------------------ host
+template <bool BWD, int B>
+static void launch_gelu_wave(const int8_t* X, const float* SX, const int8_t* G, const float* SG, int rows, int cols,
+                             int8_t* Y, float* SY, hipStream_t st) {
+  hipLaunchKernelGGL((gelu_wave_kernel<BWD, B>), dim3(tile_grid((cols / B + 3) / 4, rows / B)), dim3(256), 0, st, X, SX, G, SG,
+                     rows, cols, Y, SY);
+}
 template <bool BWD, int B, int J>
 static void launch_gelu_cfg(const int8_t* X, const float* SX, const int8_t* G, const float* SG, int rows, int cols,
                             int8_t* Y, float* SY, hipStream_t st) {
@@ -952,17 +1053,19 @@ static void launch_gelu_cfg(const int8_t* X, const float* SX, const int8_t* G, c
 template <bool BWD>
 static void launch_gelu(int block, const int8_t* X, const float* SX, const int8_t* G, const float* SG, int rows,
                         int cols, int8_t* Y, float* SY, hipStream_t st) {
-  // Workgroups of 256 columns for tensors of many rounds of workgroups (measured 6-7 % faster from HBM), of 128
-  // columns for small ones, where the shorter chain of dependent steps per workgroup counts (4 % faster at
-  // 4096 x 3072); at B = 128 a lane already holds four 8-row passes of a 128-column workgroup.
-  const bool wide = (int64_t)((cols + 127) / 128) * (rows / block) >= 8192;
+  // B = 32 / 64: one block per wave while the tensors are small enough to sit in the last-level cache (measured
+  // 10-14 % faster at 4096 x 3072; its 32- / 64-byte row pieces cost a third of the bandwidth once the data
+  // comes from HBM: crossover near 40 M elements at B = 32 and 100 M at B = 64).  Beyond that one block per
+  // workgroup column, in workgroups of 256 columns (such tensors take thousands of them; 6-7 % faster from HBM
+  // than 128 columns).  At B = 128 a lane already holds four 8-row passes of a 128-column workgroup.
+  const int64_t n = (int64_t)rows * cols;
   if (block == 128) launch_gelu_cfg<BWD, 128, 1>(X, SX, G, SG, rows, cols, Y, SY, st);
   else if (block == 64) {
-    if (wide) launch_gelu_cfg<BWD, 64, 2>(X, SX, G, SG, rows, cols, Y, SY, st);
-    else launch_gelu_cfg<BWD, 64, 1>(X, SX, G, SG, rows, cols, Y, SY, st);
+    if (n <= (int64_t(64) << 20)) launch_gelu_wave<BWD, 64>(X, SX, G, SG, rows, cols, Y, SY, st);
+    else launch_gelu_cfg<BWD, 64, 2>(X, SX, G, SG, rows, cols, Y, SY, st);
   } else {
-    if (wide) launch_gelu_cfg<BWD, 32, 2>(X, SX, G, SG, rows, cols, Y, SY, st);
-    else launch_gelu_cfg<BWD, 32, 1>(X, SX, G, SG, rows, cols, Y, SY, st);
+    if (n <= (int64_t(24) << 20)) launch_gelu_wave<BWD, 32>(X, SX, G, SG, rows, cols, Y, SY, st);
+    else launch_gelu_cfg<BWD, 32, 2>(X, SX, G, SG, rows, cols, Y, SY, st);
   }
 }
 

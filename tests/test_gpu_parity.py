@@ -309,7 +309,8 @@ def _check_eltwise(name, q, s, oq, os_, of64, block):
     say(f"  {name}: {nbad} / {oq.size} codes differ by one")
 
 
-# the last two cases are large enough for the 256-column workgroups, with a ragged last column group
+# Blocks of 32 and 64 take one block per wave up to 24 M resp. 64 M elements; the last two cases are past that and
+# run the 256-column workgroups, with a ragged last column group
 @pytest.mark.parametrize("block,N,C", [(32, 96, 352), (64, 128, 192), (128, 256, 384), (32, 4096, 3072),
                                        (32, 32768, 1120), (64, 65536, 1088)])
 def test_gelu_fwd_bwd(block, N, C):

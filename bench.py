@@ -449,13 +449,16 @@ def main():
 
     # The tensors above (6-38 MB) fit the 256 MB last-level cache, so those figures are cache/latency figures.
     # The HBM fraction of the same kernels is measured on tensors of 64x (GELU) / 256x (LayerNorm) the token
-    # count, 0.8 GB per operand, which no cache holds; values are random codes and scales drawn on the GPU.
+    # count, 0.8 GB per operand, which no cache holds; values are codes and scales drawn on the GPU.
     memops_hbm = None
     if not args.no_hbm_sized_ops:
         memops_hbm = {}
         gen = torch.Generator(device=dev)
         gen.manual_seed(240312422 + 3)
-        ri8 = lambda r, c: torch.randint(-127, 128, (r, c), generator=gen, device=dev, dtype=torch.int8)
+        # codes as per-block quantization of Gaussian data leaves them: N(0, 36^2) rounded (a block's max-abs of about
+        # 3.5 sigma maps to 127), not uniform over the byte range
+        ri8 = lambda r, c: (torch.randn((r, c), generator=gen, device=dev, dtype=torch.float16) * 36.0).round_() \
+            .clamp_(-127, 127).to(torch.int8)
         rsc = lambda r, c, m: torch.rand((r // B, c // B), generator=gen, device=dev, dtype=torch.float32) * m + 1e-3 * m
         NG, NL = 64 * N, 256 * N
         xg, sxg, gg, sgg = ri8(NG, D), rsc(NG, D, 0.06), ri8(NG, D), rsc(NG, D, 3e-5)

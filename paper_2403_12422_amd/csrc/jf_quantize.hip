@@ -26,16 +26,19 @@ struct Load4<_Float16> {
   }
 };
 
-// B = quantization block; the tile is always 128 x 128 and 256 threads.
-template <typename T, int B, bool TRANSPOSED_COPY>
-__global__ void __launch_bounds__(256) quantize_kernel(const T* __restrict__ x, int64_t ldx, int rows, int cols,
+// B = quantization block; the tile is 128 x 128 and 256 threads (WPW = 4 waves per workgroup), or, for small
+// tensors at B = 32 where the waves do not depend on each other, one 32 x 128 strip and one wave (WPW = 1), which
+// spreads a tensor of a few hundred tiles over all compute units.
+template <typename T, int B, bool TRANSPOSED_COPY, int WPW = 4>
+__global__ void __launch_bounds__(64 * WPW) quantize_kernel(const T* __restrict__ x, int64_t ldx, int rows, int cols,
                                                         int8_t* __restrict__ q, int64_t ldq, float* __restrict__ s,
                                                         int8_t* __restrict__ qT, int64_t ldqT, float* __restrict__ sT) {
   __shared__ float s_amax[4][4];                       // [32-row strip][32-col group]
   __shared__ __align__(16) uint8_t s_codes[TRANSPOSED_COPY ? 128 * 132 : 16];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const TileIndex wg = tile_of_workgroup((cols + 127) / 128);
-  const int r0 = wg.y * 128 + wave * 32;               // first row of this wave's strip
+  static_assert(WPW == 4 || (WPW == 1 && B == 32 && !TRANSPOSED_COPY), "single-wave workgroups: independent waves only");
+  const int r0 = (wg.y * WPW + wave) * 32;             // first row of this wave's strip
   const int c0 = wg.x * 128;
   const int c4 = lane & 31, rh = lane >> 5;
   const int col = c0 + 4 * c4;
@@ -55,9 +58,9 @@ __global__ void __launch_bounds__(256) quantize_kernel(const T* __restrict__ x, 
   }
   // lanes sharing a 32-column group: same c4 / 8, any c4 % 8, any rh
   amax = wave_group_max<1 | 2 | 4 | 32>(amax);
-  if ((lane & 39) == 0) s_amax[wave][c4 >> 3] = amax;
-  __syncthreads();
-  if (B > 32) {
+  if (B > 32) {  // at B = 32 a block lies inside one wave's strip: no exchange, the waves run independently
+    if ((lane & 39) == 0) s_amax[wave][c4 >> 3] = amax;
+    __syncthreads();
     constexpr int G = B / 32;  // 32-granules per block side
     const int w0 = (wave / G) * G, g0 = ((c4 >> 3) / G) * G;
     amax = 0.0f;
@@ -108,6 +111,13 @@ template <typename T, int B>
 static void launch_quantize(const T* x, int64_t ldx, int rows, int cols, int8_t* q, int64_t ldq, float* s, int8_t* qT,
                             int64_t ldqT, float* sT, hipStream_t st) {
   dim3 grid(tile_grid((cols + 127) / 128, (rows + 127) / 128));
+  if constexpr (B == 32) {
+    if (!qT && grid.x < 512) {  // fewer than two workgroups per compute unit: one wave per workgroup instead
+      hipLaunchKernelGGL((quantize_kernel<T, B, false, 1>), dim3(tile_grid((cols + 127) / 128, rows / 32)), dim3(64), 0, st, x,
+                         ldx, rows, cols, q, ldq, s, qT, ldqT, sT);
+      return;
+    }
+  }
   if (qT)
     hipLaunchKernelGGL((quantize_kernel<T, B, true>), grid, dim3(256), 0, st, x, ldx, rows, cols, q, ldq, s, qT, ldqT, sT);
   else

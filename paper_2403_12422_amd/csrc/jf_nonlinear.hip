@@ -655,8 +655,12 @@ __global__ void __launch_bounds__(512, NIT == 1 ? 3 : 2) layernorm_bwd_kernel(
       v[it] = ok[it] ? *reinterpret_cast<const uint4*>(base + (int64_t)row * cols + 16 * (lane + 64 * it)) : make_uint4(0, 0, 0, 0);
   };
 
+  // row statistics are the same for all lanes of a wave: scalar loads (the vectors are not written by this kernel)
+  typedef const __attribute__((address_space(4))) float* const_f32_ptr;
+  const const_f32_ptr mean_c = (const_f32_ptr)mean_in, rstd_c = (const_f32_ptr)rstd_in;
   for (int bi = blockIdx.x; bi < rows / B; bi += gridDim.x) {
     const int r0 = bi * B + wave * RW;
+    const int r0u = __builtin_amdgcn_readfirstlane(r0);
     float sx[NIT], sgv[NIT], mloc[NIT];
 #pragma unroll
     for (int it = 0; it < NIT; ++it) {
@@ -679,7 +683,7 @@ __global__ void __launch_bounds__(512, NIT == 1 ? 3 : 2) layernorm_bwd_kernel(
         load_row(X, r0 + r + 1, nx);
         load_row(G, r0 + r + 1, ng);
       }
-      const float mu = mean_in[r0 + r], rs = rstd_in[r0 + r];
+      const float mu = mean_c[r0u + r], rs = rstd_c[r0u + r];
       const float mrs = -mu * rs;
       float m1 = 0.0f, m2 = 0.0f;
       float xh[NIT][16], gh[NIT][16];
@@ -748,7 +752,7 @@ __global__ void __launch_bounds__(512, NIT == 1 ? 3 : 2) layernorm_bwd_kernel(
         load_row(X, r0 + r + 1, nx);
         load_row(G, r0 + r + 1, ng);
       }
-      const float mu = mean_in[r0 + r], rs = rstd_in[r0 + r];
+      const float mu = mean_c[r0u + r], rs = rstd_c[r0u + r];
       const float mrs = -mu * rs;
       const float q1 = s_q[2 * (wave * RW + r)], q2 = s_q[2 * (wave * RW + r) + 1];
 #pragma unroll

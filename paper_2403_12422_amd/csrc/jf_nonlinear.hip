@@ -1011,25 +1011,26 @@ __global__ void __launch_bounds__(1024) layernorm_bwd_wide_kernel(const int8_t* 
 }
 
 // dgamma / dbeta: sum the per-wave partial rows in a fixed order (bit-stable from run to run).  A workgroup
-// of 16 waves owns 64 columns of the 2*C wide partial matrix; wave w sums rows w, w+16, w+32, ... (four
+// of 16 waves owns 64 columns of the 2*C wide partial matrix; wave w sums rows w, w+16, w+32, ... (eight
 // independent chains keep loads in flight), and wave 0 adds the 16 results in wave order.
 __global__ void __launch_bounds__(1024) colsum_kernel(const float* __restrict__ partials, int nparts, int cols2,
                                                        float* __restrict__ dgamma, float* __restrict__ dbeta) {
   __shared__ float s_part[16][64];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int c = blockIdx.x * 64 + lane;
-  float acc0 = 0.0f, acc1 = 0.0f, acc2 = 0.0f, acc3 = 0.0f;
+  float acc[8] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
   if (c < cols2) {
     int p = wave;
-    for (; p + 48 < nparts; p += 64) {
-      acc0 += partials[(int64_t)p * cols2 + c];
-      acc1 += partials[(int64_t)(p + 16) * cols2 + c];
-      acc2 += partials[(int64_t)(p + 32) * cols2 + c];
-      acc3 += partials[(int64_t)(p + 48) * cols2 + c];
+    for (; p + 112 < nparts; p += 128) {
+      float v[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) v[j] = partials[(int64_t)(p + 16 * j) * cols2 + c];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) acc[j] += v[j];
     }
-    for (; p < nparts; p += 16) acc0 += partials[(int64_t)p * cols2 + c];
+    for (; p < nparts; p += 16) acc[0] += partials[(int64_t)p * cols2 + c];
   }
-  s_part[wave][lane] = (acc0 + acc1) + (acc2 + acc3);
+  s_part[wave][lane] = ((acc[0] + acc[1]) + (acc[2] + acc[3])) + ((acc[4] + acc[5]) + (acc[6] + acc[7]));
   __syncthreads();
   if (wave == 0 && c < cols2) {
     float v = 0.0f;

@@ -87,3 +87,12 @@ def test_binding_refuses_cpu_tensors():
     import torch
     with pytest.raises(binding.JetfireError):
         binding.jf_quantize_block(torch.zeros(64, 64), 32)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The benchmark is a one-GPU program: asking for more exits with a message before anything touches a GPU."""
+    import subprocess
+    import sys
+    res = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert res.returncode != 0
+    assert "one GPU" in (res.stderr + res.stdout)

@@ -96,3 +96,23 @@ def test_bench_refuses_more_than_one_gpu():
     res = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
     assert res.returncode != 0
     assert "one GPU" in (res.stderr + res.stdout)
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    """No fallback: without the built shared object the first call raises and names the build step."""
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "_LIB_PATH", str(tmp_path / "libjetfire.so"))
+    with pytest.raises(binding.JetfireError, match="no CPU fallback"):
+        binding.load_library()
+    with pytest.raises(binding.JetfireError):
+        binding.jf_workspace_bytes(binding.JF_OP_LAYERNORM_BWD, 64, 64, 0, 32)
+
+
+def test_nothing_in_the_product_imports_the_oracle():
+    """The oracle is test infrastructure: the package itself never imports it."""
+    pkg = os.path.join(ROOT, "paper_2403_12422_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".hpp", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "import oracle" not in text and "from oracle" not in text and "oracle/" not in text, f

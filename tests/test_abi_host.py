@@ -116,3 +116,12 @@ def test_nothing_in_the_product_imports_the_oracle():
             if f.endswith((".py", ".hip", ".hpp", ".h")):
                 text = open(os.path.join(dirpath, f)).read()
                 assert "import oracle" not in text and "from oracle" not in text and "oracle/" not in text, f
+
+
+def test_oracle_shares_nothing_with_the_product():
+    """The oracle neither imports the package nor includes its headers or kernels."""
+    odir = os.path.join(ROOT, "oracle")
+    for f in os.listdir(odir):
+        if f.endswith((".py", ".c", ".h")):
+            text = open(os.path.join(odir, f)).read()
+            assert "paper_2403_12422_amd" not in text and "jetfire.h" not in text and "csrc" not in text, f

@@ -438,6 +438,15 @@ def main():
     ops["add_with_row_partials"] = (lambda: jf.jf_add_q(Y, SY, H, SH, B, want_partials=True, out=(dY, SdY, rm, rq)),
                                     N * D * (3 + 3 * sb + 8.0 / B))
     ops["dropout"] = (lambda: jf.jf_dropout_q(Y, SY, mask_bits, 0.1, B, out=(dY, SdY)), N * D * (2.125 + 2 * sb))
+    # LayerNorm whose statistics come from the row partials of the preceding Add (the paper's own LayerNorm design):
+    # partials of the 4096 x 768 input written by an Add of it with a zero tensor
+    zq, zs = torch.zeros_like(Xq), torch.zeros_like(SX)
+    xr, sxr = torch.empty_like(Xq), torch.empty_like(SX)
+    pm, pq = (torch.empty((N, C // B), dtype=torch.float32, device=dev) for _ in range(2))
+    jf.jf_add_q(Xq, SX, zq, zs, B, want_partials=True, out=(xr, sxr, pm, pq))
+    ops["layernorm_fwd_from_row_partials"] = (
+        lambda: jf.jf_layernorm_q_partials(xr, sxr, pm, pq, gamma, beta, 1e-5, B, out=(Xn, SXn, mean, rstd)),
+        N * C * (2 + 2 * sb + 8.0 / B) + 8 * N + 8 * C)
     # the hand-over to a floating-point operator (the FP16 attention core): INT8 -> FP16
     h16 = torch.empty((N, D), dtype=torch.float16, device=dev)
     ops["dequantize_f16"] = (lambda: jf.jf_dequantize_block(Y, SY, B, dtype=torch.float16, out=h16), N * D * (3 + sb))

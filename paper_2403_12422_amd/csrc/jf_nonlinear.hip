@@ -457,7 +457,9 @@ __device__ __forceinline__ void load16f(const float* p, float (&v)[16]) {
 
 // Forward: NW = 16 waves per workgroup (a workgroup is alone on its compute unit, since there are only
 // N/B of them), RW = B/16 rows per wave.  If the wave's rows fit in registers (KEEP) they are read once.
-template <int B, int NIT>
+// FROM_PARTIALS: the row statistics come from the row partials of the preceding Add (row_mean, row_sumsq) instead
+// of the codes.
+template <int B, int NIT, bool FROM_PARTIALS>
 __global__ void __launch_bounds__(1024) layernorm_fwd_kernel(const int8_t* __restrict__ X, const float* __restrict__ SX,
                                                               const float* __restrict__ gamma,
                                                               const float* __restrict__ beta, float eps, int rows,
@@ -504,14 +506,27 @@ __global__ void __launch_bounds__(1024) layernorm_fwd_kernel(const int8_t* __res
   // the wave without loss.  (Two FP32 butterflies instead of two FP64 ones: a quarter of the instructions.)
   float k1[RW][NIT], k2[RW];  // xhat = u * k1 + k2 with u = code + 128
   const float inv_cols_f = (float)inv_cols;
+  // Statistics handed over by the preceding Add (App. A): per row and block column the mean and the sum of squares
+  // over the block's B columns.  All of the wave's rows are requested at once, beside the codes.
+  constexpr int NJ = (NIT * 1024 / B + 63) / 64;  // block columns per lane
+  float pm[RW][NJ], pq[RW][NJ];
+  if constexpr (FROM_PARTIALS) {
+#pragma unroll
+    for (int r = 0; r < RW; ++r)
+#pragma unroll
+      for (int jj = 0; jj < NJ; ++jj) {
+        const int j = lane + 64 * jj;
+        pm[r][jj] = j < lc ? row_mean[(int64_t)(r0 + r) * lc + j] : 0.0f;
+        pq[r][jj] = j < lc ? row_sumsq[(int64_t)(r0 + r) * lc + j] : 0.0f;
+      }
+  }
 #pragma unroll
   for (int r = 0; r < RW; ++r) {
     double cs[NIT], cq[NIT];  // per chunk: sum and sum of squares of the dequantized values
     double ds = 0.0;
-    if (row_mean != nullptr) {
-      // statistics handed over by the preceding Add (App. A): per block column the mean and the sum of
-      // squares over its B columns; a block's sum is B times its mean
-      for (int j = lane; j < lc; j += 64) ds += (double)B * (double)row_mean[(int64_t)(r0 + r) * lc + j];
+    if constexpr (FROM_PARTIALS) {
+#pragma unroll
+      for (int jj = 0; jj < NJ; ++jj) ds += (double)B * (double)pm[r][jj];  // a block's sum is B times its mean
     } else {
 #pragma unroll
       for (int it = 0; it < NIT; ++it) {
@@ -529,11 +544,11 @@ __global__ void __launch_bounds__(1024) layernorm_fwd_kernel(const int8_t* __res
     const float mu = wave_group_sum<63>((float)ds) * inv_cols_f;
     const double mud = (double)mu;
     double dv = 0.0;
-    if (row_mean != nullptr) {
-      for (int j = lane; j < lc; j += 64) {
-        const double bs = (double)B * (double)row_mean[(int64_t)(r0 + r) * lc + j];
-        dv += (double)row_sumsq[(int64_t)(r0 + r) * lc + j] - 2.0 * mud * bs + (double)B * mud * mud;
-      }
+    if constexpr (FROM_PARTIALS) {
+#pragma unroll
+      for (int jj = 0; jj < NJ; ++jj)
+        if (lane + 64 * jj < lc)
+          dv += (double)pq[r][jj] - 2.0 * mud * ((double)B * (double)pm[r][jj]) + (double)B * mud * mud;
     } else {
 #pragma unroll
       for (int it = 0; it < NIT; ++it)
@@ -1087,8 +1102,9 @@ static int32_t check_eltwise(const void* x, const void* sx, const void* y, const
 constexpr int64_t kLayerNormMaxC = 4096;
 
 template <int B, int NIT, typename... Args>
-static void launch_ln_fwd(dim3 grid, size_t lds, hipStream_t st, Args... args) {
-  hipLaunchKernelGGL((layernorm_fwd_kernel<B, NIT>), grid, dim3(1024), lds, st, args...);
+static void launch_ln_fwd(bool from_partials, dim3 grid, size_t lds, hipStream_t st, Args... args) {
+  if (from_partials) hipLaunchKernelGGL((layernorm_fwd_kernel<B, NIT, true>), grid, dim3(1024), lds, st, args...);
+  else hipLaunchKernelGGL((layernorm_fwd_kernel<B, NIT, false>), grid, dim3(1024), lds, st, args...);
 }
 template <int B, int NIT, typename... Args>
 static void launch_ln_bwd(dim3 grid, size_t lds, hipStream_t st, Args... args) {
@@ -1148,7 +1164,7 @@ static int32_t layernorm_fwd(const int8_t* X, const float* SX, const float* row_
   const dim3 grid((unsigned)(N / block));
   const int nit = (int)((C + 1023) / 1024);
   const size_t lds = 16 * (size_t)(C / 32) * sizeof(float);
-  JF_LN_DISPATCH(launch_ln_fwd, block, nit, grid, lds, st, X, SX, gamma, beta, eps, (int)N, (int)C, Y, SY, mean, rstd,
+  JF_LN_DISPATCH(launch_ln_fwd, block, nit, row_mean != nullptr, grid, lds, st, X, SX, gamma, beta, eps, (int)N, (int)C, Y, SY, mean, rstd,
                  row_mean, row_sumsq);
   return launch_status();
 }

@@ -450,6 +450,9 @@ def main():
     # the hand-over to a floating-point operator (the FP16 attention core): INT8 -> FP16
     h16 = torch.empty((N, D), dtype=torch.float16, device=dev)
     ops["dequantize_f16"] = (lambda: jf.jf_dequantize_block(Y, SY, B, dtype=torch.float16, out=h16), N * D * (3 + sb))
+    # and back: the quantizer on an FP16 tensor (what the attention core hands over)
+    a16 = dH.to(torch.float16)
+    ops["quantize_f16"] = (lambda: jf.jf_quantize_block(a16, B, out=(Gq, SG)), N * D * (3 + sb))
     memops = {}
     for name, (fn, nbytes) in ops.items():
         ms = op_ms(fn)

@@ -490,11 +490,12 @@ __global__ void __launch_bounds__(64 * WGM * WGN, WMIN) gemm_kernel(const GemmAr
   };
 
   static_assert(NBUF >= 3, "a prefetched stage implies the stage whose scales are requested");
-  advance_scales(true, (rem ? rem : SPS) / KPB);
-  advance_scales(t0 + 1 <= tl, NKB);
+  // the tiles of the first stages are requested before the scales: the second scale request waits for the first
 #pragma unroll
   for (int i = 0; i < AHEAD; ++i)
     if (t0 + i <= tl) issue(t0 + i, slot_of(t0 + i));
+  advance_scales(true, (rem ? rem : SPS) / KPB);
+  advance_scales(t0 + 1 <= tl, NKB);
   wait_loads(t0 + AHEAD - 1 <= tl);
   if (t0 + AHEAD <= tl) issue(t0 + AHEAD, slot_of(t0 + AHEAD));
   advance_scales(t0 + 2 <= tl, NKB);

@@ -122,19 +122,32 @@ __device__ __forceinline__ double wave_group_sum_f64(double v) {
                                  [](double x, auto bit) { return lane_xor_f64<decltype(bit)::value>(x); });
 }
 
-// Eq. 1 scale of a block from its max-abs: one IEEE FP32 division; 0 for an
-// all-zero block.  `inv` is the factor codes are multiplied with (0 if the
-// block is all zero, so that every code becomes 0).
-__device__ __forceinline__ void block_scale(float amax, float& scale, float& inv) {
+// Eq. 1 scale of a block from its max-abs: one IEEE FP32 division; 0 for an all-zero block.  `inv` is the
+// reciprocal of the scale in double precision (0 for an all-zero block, so that every code becomes 0): the
+// hardware estimate refined by two Newton steps, relative error below 2^-50.  The double reciprocal exists for
+// every FP32 scale, subnormal ones included.
+__device__ __forceinline__ void block_scale(float amax, float& scale, double& inv) {
   scale = amax / 127.0f;
-  inv = amax > 0.0f ? 1.0f / scale : 0.0f;
+  const double s = (double)scale;
+  double r = __builtin_amdgcn_rcp(s);
+  r = __builtin_fma(__builtin_fma(-s, r, 1.0), r, r);
+  r = __builtin_fma(__builtin_fma(-s, r, 1.0), r, r);
+  inv = scale > 0.0f ? r : 0.0;
 }
 
-// round-half-even(x * inv) as an integer in the low byte of the result:
-// adding 1.5 * 2^23 inside one fused multiply-add leaves the rounded integer
-// in the low mantissa bits (two's complement modulo 256 in bits 0..7).
-__device__ __forceinline__ uint32_t code_bits(float x, float inv) {
-  return __float_as_uint(__builtin_fmaf(x, inv, 12582912.0f));
+// round-half-even(x / scale) of the EXACT quotient of the two FP32 numbers (Eq. 1), as an integer in the low
+// byte of the result.  A quotient of two FP32 numbers is either exactly k + 1/2 or at least 2^-26 away from it,
+// so it suffices to know it to better than that, which x * inv in double does (error below 127.5 * 2^-50):
+//   t1 = fma(x, inv, 1.5 * 2^20)    lies in one binade with ulp 2^-32: everything within 2^-33 of k + 1/2 -- only
+//                                   exact ties are -- lands exactly on the tie, everything else stays on its side;
+//   t  = t1 + (1.5 * 2^52 - 1.5 * 2^20)   rounds to an integer, the exact tie to even (1.5 * 2^52 is even), and
+//                                   leaves it in the low mantissa bits (two's complement modulo 256 in bits 0..7).
+// An FP32 product x * (1/scale) cannot do this: its error of up to 7.6e-6 decides every tie and near-tie at
+// random, and tensors whose blocks keep their scale through an operator consist of little else.
+__device__ __forceinline__ uint32_t code_bits(float x, double inv) {
+  const double t1 = __builtin_fma((double)x, inv, 1572864.0);
+  const double t = t1 + (6755399441055744.0 - 1572864.0);
+  return (uint32_t)__builtin_bit_cast(unsigned long long, t);
 }
 
 // Pack the low bytes of four code_bits() results into one dword, a0 lowest.
@@ -144,7 +157,7 @@ __device__ __forceinline__ uint32_t pack_codes(uint32_t a0, uint32_t a1, uint32_
   return lo | hi;
 }
 
-__device__ __forceinline__ uint32_t quantize4(float x0, float x1, float x2, float x3, float inv) {
+__device__ __forceinline__ uint32_t quantize4(float x0, float x1, float x2, float x3, double inv) {
   return pack_codes(code_bits(x0, inv), code_bits(x1, inv), code_bits(x2, inv), code_bits(x3, inv));
 }
 

@@ -571,8 +571,11 @@ __global__ void __launch_bounds__(64 * WGM * WGN, WMIN) gemm_kernel(const GemmAr
       }
   }
   const int ln = g.Nn / B;
-  // The code tile is staged in the (now idle) operand ring: in one slot, or split by rows over two slots when
-  // a slot is smaller than the tile.
+  // The code tile is staged in the operand ring: in one slot, or split by rows over two slots when a slot is
+  // smaller than the tile.  The last stage of the K loop ends without a barrier, so a wave may still be reading its
+  // fragments of that stage out of the ring while a faster one is already here: meet once before the ring is
+  // overwritten (for B > 32 the barrier of the max-abs exchange above has done that).
+  if (B == 32 && g.Oq != nullptr) __syncthreads();
   constexpr int CODE_ROWS_PER_SLOT = TM * TN <= STAGE_BYTES ? TM : TM / 2;
   static_assert(CODE_ROWS_PER_SLOT * TN <= STAGE_BYTES, "half the code tile fits a ring slot");
   auto code_row = [&](int row) __attribute__((always_inline)) -> int8_t* {
@@ -593,12 +596,12 @@ __global__ void __launch_bounds__(64 * WGM * WGN, WMIN) gemm_kernel(const GemmAr
               make_float4(acc[a][b][4 * q4], acc[a][b][4 * q4 + 1], acc[a][b][4 * q4 + 2], acc[a][b][4 * q4 + 3]);
       }
       if (g.Oq) {
-        float scale, inv;
+        float scale;
+        double inv;
         block_scale(amax[a][b], scale, inv);
         if (lane == 0 && (mrow0 % B) == 0 && (ncol0 % B) == 0) g.Os[(int64_t)(mrow0 / B) * ln + ncol0 / B] = scale;
-        // Codes go to LDS first (the operand ring is idle now: every wave has passed the last stage barrier),
-        // laid out as the TM x TN byte tile with its 16-byte chunks XOR-swizzled by the row, so that the
-        // tile can be written to memory as whole rows.
+        // Codes go to LDS first, laid out as the TM x TN byte tile with its 16-byte chunks XOR-swizzled by the
+        // row, so that the tile can be written to memory as whole rows.
         const int row = 32 * (wm0 + a) + (lane & 31);
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {

@@ -59,7 +59,7 @@ __device__ __forceinline__ float amax4(float m, float a, float b, float c, float
   return fmaxf(fmaxf(m, fmaxf(fabsf(a), fabsf(b))), fmaxf(fabsf(c), fabsf(d)));
 }
 
-__device__ __forceinline__ uint4 quantize16(const float (&y)[16], float inv) {
+__device__ __forceinline__ uint4 quantize16(const float (&y)[16], double inv) {
   uint4 o;
   o.x = quantize4(y[0], y[1], y[2], y[3], inv);
   o.y = quantize4(y[4], y[5], y[6], y[7], inv);
@@ -156,7 +156,9 @@ __global__ void __launch_bounds__(256) gelu_kernel(const int8_t* __restrict__ X,
           pos = a - aq;
           neg = 0.0f - aq;
         }
-        s_tab[k][i] = pos;
+        // code 0: GELU(0) = 0 comes out exactly; GELU'(0) = 1/2 is set, because the tail fit is only good to 4e-8
+        // there and a derivative of 0.49999994 would push every halved gradient code off its rounding tie
+        s_tab[k][i] = (BWD && i == 0) ? 0.5f : pos;
         s_tab[k][i == 0 ? 128 : 256 - i] = i == 0 ? 0.0f : neg;
       }
     }
@@ -207,7 +209,8 @@ __global__ void __launch_bounds__(256) gelu_kernel(const int8_t* __restrict__ X,
   for (int j = 0; j < J; ++j) {
     const int gi = 4 * j + (ch >> 1);
     const float m = fmaxf(fmaxf(s_amax[0][gi], s_amax[1][gi]), fmaxf(s_amax[2][gi], s_amax[3][gi]));
-    float scale, inv;
+    float scale;
+    double inv;
     block_scale(m, scale, inv);
     if (!col_ok[j]) continue;
     if (wave == 0 && rsub == 0 && (col[j] % B) == 0) SY[(int64_t)bi * lc + col[j] / B] = scale;
@@ -267,7 +270,7 @@ __global__ void __launch_bounds__(256) gelu_wave_kernel(const int8_t* __restrict
       pos = a - aq;
       neg = 0.0f - aq;
     }
-    tab[i] = pos;
+    tab[i] = (BWD && i == 0) ? 0.5f : pos;  // GELU'(0) = 1/2 exactly, see gelu_kernel
     tab[i == 0 ? 128 : 256 - i] = i == 0 ? 0.0f : neg;
   }
   // The table is written and read by this wave only; LDS serves a wave's accesses in program order, and the
@@ -307,7 +310,8 @@ __global__ void __launch_bounds__(256) gelu_wave_kernel(const int8_t* __restrict
     for (int e = 0; e < 16; e += 4) m = amax4(m, y[p][e], y[p][e + 1], y[p][e + 2], y[p][e + 3]);
   }
   m = wave_group_max<63>(m);
-  float scale, inv;
+  float scale;
+  double inv;
   block_scale(m, scale, inv);
   if (lane == 0) SY[(int64_t)bi * lc + bj] = scale;
 #pragma unroll
@@ -368,7 +372,8 @@ __global__ void __launch_bounds__(256) add_kernel(const int8_t* __restrict__ X1,
   if ((lane & 57) == 0) s_amax[wave][ch >> 1] = m;
   __syncthreads();
   m = fmaxf(fmaxf(s_amax[0][ch >> 1], s_amax[1][ch >> 1]), fmaxf(s_amax[2][ch >> 1], s_amax[3][ch >> 1]));
-  float scale, inv;
+  float scale;
+  double inv;
   block_scale(m, scale, inv);
   if (!col_ok) return;
   if (wave == 0 && rsub == 0 && (col % B) == 0) SY[(int64_t)bi * lc + col / B] = scale;
@@ -418,7 +423,8 @@ __global__ void __launch_bounds__(256) dropout_kernel(const int8_t* __restrict__
   if ((lane & 57) == 0) s_amax[wave][ch >> 1] = m;
   __syncthreads();
   m = fmaxf(fmaxf(s_amax[0][ch >> 1], s_amax[1][ch >> 1]), fmaxf(s_amax[2][ch >> 1], s_amax[3][ch >> 1]));
-  float scale, inv;
+  float scale;
+  double inv;
   block_scale(m, scale, inv);
   if (!col_ok) return;
   if (wave == 0 && rsub == 0 && (col % B) == 0) SY[(int64_t)bi * lc + col / B] = scale;
@@ -604,7 +610,8 @@ __global__ void __launch_bounds__(1024) layernorm_fwd_kernel(const int8_t* __res
   for (int it = 0; it < NIT; ++it) {
     const int c = lane + 64 * it;
     if (ok[it]) {
-      float mm = 0.0f, scale, inv;
+      float mm = 0.0f, scale;
+      double inv;
 #pragma unroll
       for (int w = 0; w < NW; ++w) mm = fmaxf(mm, s_amax[w * ngran + (c >> 1)]);
       block_scale(mm, scale, inv);
@@ -744,7 +751,7 @@ __global__ void __launch_bounds__(512, NIT == 1 ? 3 : 2) layernorm_bwd_kernel(
     __syncthreads();
 
     // ---- pass B
-    float inv[NIT];
+    double inv[NIT];
 #pragma unroll
     for (int it = 0; it < NIT; ++it) {
       const int c = lane + 64 * it;
@@ -1002,7 +1009,8 @@ __global__ void __launch_bounds__(1024) layernorm_bwd_wide_kernel(const int8_t* 
   for (int it = 0; it < NIT; ++it) {
     const int c = lane + 64 * it;
     if (ok[it]) {
-      float mm = 0.0f, scale, inv;
+      float mm = 0.0f, scale;
+      double inv;
 #pragma unroll
       for (int w = 0; w < NW; ++w) mm = fmaxf(mm, s_amax[w * ngran + (c >> 1)]);
       block_scale(mm, scale, inv);

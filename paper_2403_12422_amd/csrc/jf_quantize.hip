@@ -69,7 +69,8 @@ __global__ void __launch_bounds__(64 * WPW) quantize_kernel(const T* __restrict_
 #pragma unroll
       for (int b = 0; b < G; ++b) amax = fmaxf(amax, s_amax[w0 + a][g0 + b]);
   }
-  float scale, inv;
+  float scale;
+  double inv;
   block_scale(amax, scale, inv);
 
   const int lr = rows / B, lc = cols / B;

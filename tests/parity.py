@@ -4,7 +4,9 @@ Tolerances (from the benchmark spec of this build):
   * INT32 block partial sums: bit-exact;
   * re-quantized INT8 codes: identical except +-1 at rounding ties on at most 0.1 % of the elements;
   * scales and FP32 outputs: 1e-5 relative (FP32 outputs relative to the max-abs of their quantization block,
-    which is what the quantizer sees; element-wise relative error is meaningless where the sum cancels).
+    which is what the quantizer sees; element-wise relative error is meaningless where the sum cancels);
+  * column sums (dgamma, dbeta of LayerNorm backward): FP32 sums of N signed terms, 1e-5 relative to the sum of
+    the terms' magnitudes -- the one rule for them in every test.
 """
 import numpy as np
 
@@ -61,3 +63,14 @@ def assert_f32_close(got, want64, block, what=""):
     big = (np.abs(want64) >= 1e-2 * amax) & (amax > 0)
     rel = err[big] / np.abs(want64[big])
     assert rel.size == 0 or rel.max() <= 1e-3, f"{what}: element-wise rel err {rel.max():.3e}"
+
+
+def assert_layernorm_param_grads_close(dgamma, dbeta, want_dgamma, want_dbeta, g64, xhat64, what=""):
+    """dgamma = sum_N g * xhat and dbeta = sum_N g against the oracle's double sums: within REL_TOL of the sum of
+    the magnitudes of the terms (g64, xhat64: the dequantized upstream gradient and the normalised input)."""
+    tol_g = REL_TOL * np.abs(g64 * xhat64).sum(axis=0) + 1e-30
+    tol_b = REL_TOL * np.abs(g64).sum(axis=0) + 1e-30
+    err_g = np.abs(np.asarray(dgamma, np.float64) - want_dgamma)
+    err_b = np.abs(np.asarray(dbeta, np.float64) - want_dbeta)
+    assert np.all(err_g <= tol_g), f"{what}: dgamma error / tolerance {np.max(err_g / tol_g):.3f}"
+    assert np.all(err_b <= tol_b), f"{what}: dbeta error / tolerance {np.max(err_b / tol_b):.3f}"

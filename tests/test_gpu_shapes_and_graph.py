@@ -7,6 +7,7 @@ import torch
 import oracle
 import paper_2403_12422_amd as jf
 from paper_2403_12422_amd import workloads
+from parity import assert_layernorm_param_grads_close
 from test_gpu_parity import _check_eltwise, _check_linear, dev, host, say
 
 pytestmark = pytest.mark.gpu
@@ -48,8 +49,8 @@ def test_random_shapes_every_operator(case):
     o = oracle.layernorm_q_bwd(X2, SX2, X, SX, gamma, omean, orstd, block)
     got = jf.jf_layernorm_q_bwd(X2d, SX2d, Xd, SXd, gd, dev(omean), dev(orstd), block)
     _check_eltwise("layernorm bwd", got[0], got[1], o[0], o[1], o[4], block)
-    np.testing.assert_allclose(host(got[2]), o[2], rtol=0, atol=1e-4 * max(np.abs(o[2]).max(), 1e-30))
-    np.testing.assert_allclose(host(got[3]), o[3], rtol=0, atol=1e-4 * max(np.abs(o[3]).max(), 1e-30))
+    xh = (oracle.dequantize(X, SX, block) - omean[:, None].astype(np.float64)) * orstd[:, None].astype(np.float64)
+    assert_layernorm_param_grads_close(host(got[2]), host(got[3]), o[2], o[3], oracle.dequantize(X2, SX2, block), xh, "layernorm bwd")
     np.testing.assert_array_equal(host(jf.jf_dequantize_block(Xd, SXd, block)), oracle.dequantize(X, SX, block).astype(np.float32))
 
 

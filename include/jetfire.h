@@ -204,6 +204,27 @@ int32_t jf_layernorm_q_bwd(const int8_t* dY, const float* SdY, const int8_t* X, 
                            float* SdX, float* dgamma, float* dbeta, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * jf_layernorm_q_bwd for callers that cannot allocate device memory and so have
+ * no workspace to hand over: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, results and kernels as
+ * jf_layernorm_q_bwd, bit for bit, without `ws` / `ws_bytes`: the partial rows
+ * of dgamma | dbeta live in a static device array of JF_STATIC_SCRATCH_BYTES
+ * inside the library (one copy per GPU, held until the process ends).  The call
+ * allocates and frees nothing.  Problems whose
+ * jf_workspace_bytes(JF_OP_LAYERNORM_BWD, N, C, 0, block) exceeds
+ * JF_STATIC_SCRATCH_BYTES are rejected with JF_ERR_WORKSPACE (every N is
+ * accepted up to C = 2048; 2048 < C <= 4096 up to N / block = 64 row blocks).
+ * All calls on one GPU share that GPU's array: calls that overlap in time on
+ * one GPU (different streams or threads) race; calls on one stream do not.
+ * The first call on a device looks the array's address up
+ * (hipGetSymbolAddress), so make it outside graph capture.
+ */
+#define JF_STATIC_SCRATCH_BYTES (8u << 20)
+int32_t jf_layernorm_q_bwd_static(const int8_t* dY, const float* SdY, const int8_t* X, const float* SX,
+                                  const float* gamma, const float* mean, const float* rstd, int64_t N, int64_t C,
+                                  int32_t block, int8_t* dX, float* SdX, float* dgamma, float* dbeta, void* stream);
+
+/*
  * Test hook (Sec. 5.3, first equation): the INT32 product of K-block `kb`
  * for the whole output of one of the three GEMMs, computed by the same
  * staging / MFMA code as the production kernels.

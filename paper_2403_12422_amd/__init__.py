@@ -16,6 +16,7 @@ from .binding import (  # noqa: F401
     jf_gelu_q_bwd,
     jf_layernorm_q,
     jf_layernorm_q_bwd,
+    jf_layernorm_q_bwd_static,
     jf_layernorm_q_partials,
     jf_linear_dgrad,
     jf_linear_fwd,

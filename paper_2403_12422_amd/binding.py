@@ -29,6 +29,7 @@ _SIGNATURES = {
     "jf_dropout_q": (_I32, [_P, _P, _P, _F32, _I64, _I64, _I32, _P, _P, _P]),
     "jf_add_q": (_I32, [_P, _P, _P, _P, _I64, _I64, _I32, _P, _P, _P, _P, _P]),
     "jf_layernorm_q_bwd": (_I32, [_P, _P, _P, _P, _P, _P, _P, _I64, _I64, _I32, _P, _P, _P, _P, _P, _SZ, _P]),
+    "jf_layernorm_q_bwd_static": (_I32, [_P, _P, _P, _P, _P, _P, _P, _I64, _I64, _I32, _P, _P, _P, _P, _P]),
     "jf_debug_linear_partials": (_I32, [_I32, _P, _P, _I64, _I64, _I64, _I32, _I64, _P, _P]),
     "jf_debug_set_gemm_shape": (_I32, [_I32]),
 }
@@ -279,6 +280,22 @@ def jf_layernorm_q_bwd(dY, SdY, X, SX, gamma, mean, rstd, block=32, workspace=No
     _check(load_library().jf_layernorm_q_bwd(_ptr(dY), _ptr(SdY), _ptr(X), _ptr(SX), _ptr(gamma), _ptr(mean),
                                              _ptr(rstd), N, C, block, _ptr(dX), _ptr(SdX), _ptr(dgamma), _ptr(dbeta),
                                              _ptr(workspace), workspace.numel(), _stream()))
+    return dX, SdX, dgamma, dbeta
+
+
+def jf_layernorm_q_bwd_static(dY, SdY, X, SX, gamma, mean, rstd, out, block=32):
+    """jf_layernorm_q_bwd without a workspace: the library's static device scratch holds the partial sums, and
+    nothing is allocated -- `out` = (dX, SdX, dgamma, dbeta), preallocated, is therefore required."""
+    _dev(X, torch.int8, 2), _dev(SX, torch.float32, 2), _dev(dY, torch.int8, 2), _dev(SdY, torch.float32, 2)
+    _dev(gamma, torch.float32, 1), _dev(mean, torch.float32, 1), _dev(rstd, torch.float32, 1)
+    N, C = X.shape
+    if dY.shape != X.shape:
+        raise JetfireError(2, "dY and X shapes differ")
+    dX, SdX, dgamma, dbeta = out
+    _dev(dX, torch.int8, 2), _dev(SdX, torch.float32, 2), _dev(dgamma, torch.float32, 1), _dev(dbeta, torch.float32, 1)
+    _check(load_library().jf_layernorm_q_bwd_static(_ptr(dY), _ptr(SdY), _ptr(X), _ptr(SX), _ptr(gamma), _ptr(mean),
+                                                    _ptr(rstd), N, C, block, _ptr(dX), _ptr(SdX), _ptr(dgamma),
+                                                    _ptr(dbeta), _stream()))
     return dX, SdX, dgamma, dbeta
 
 

@@ -7,6 +7,8 @@
 //     indexed by its code byte -- the dequantize step of Alg. 2 and the erf evaluation collapse into it;
 //   * LayerNorm: row sums come from exact integer dot products of the codes (v_dot4), scaled per block,
 //     which is the row-partials scheme of App. A applied to the INT8 input itself.
+#include <mutex>
+
 #include "jf_common.hpp"
 
 namespace jf {
@@ -1227,10 +1229,29 @@ extern "C" int32_t jf_add_q(const int8_t* X1, const float* S1, const int8_t* X2,
   return launch_status();
 }
 
-extern "C" int32_t jf_layernorm_q_bwd(const int8_t* dY, const float* SdY, const int8_t* X, const float* SX,
-                                      const float* gamma, const float* mean, const float* rstd, int64_t N, int64_t C,
-                                      int32_t block, int8_t* dX, float* SdX, float* dgamma, float* dbeta, void* ws,
-                                      size_t ws_bytes, void* stream) {
+// LayerNorm backward behind both entry points: `partials` is the caller's workspace or this library's static
+// scratch; every argument has been validated.
+static int32_t layernorm_bwd_launch(const int8_t* dY, const float* SdY, const int8_t* X, const float* SX,
+                                    const float* gamma, const float* mean, const float* rstd, int64_t N, int64_t C,
+                                    int32_t block, int8_t* dX, float* SdX, float* dgamma, float* dbeta, float* partials,
+                                    hipStream_t st) {
+  using namespace jf;
+  const int nparts = (int)ln_bwd_partial_rows(N, C, block);
+  const dim3 grid((unsigned)(C > 2048 ? N / block : nparts));
+  const int nit = (int)((C + 1023) / 1024);
+  // max-abs slots per wave, (row means,) four column-sum rows
+  const size_t lds = C > 2048 ? (16 * (size_t)(C / 32) + 4 * 2 * (size_t)C) * sizeof(float)
+                              : (8 * (size_t)(C / 32) + 2 * (size_t)block + 4 * 2 * (size_t)C) * sizeof(float);
+  JF_LN_DISPATCH(launch_ln_bwd, block, nit, grid, lds, st, dY, SdY, X, SX, gamma, mean, rstd, (int)N, (int)C, dX, SdX, partials);
+  const int32_t rc = launch_status();
+  if (rc != JF_OK) return rc;
+  hipLaunchKernelGGL(colsum_kernel, dim3((unsigned)((2 * C + 63) / 64)), dim3(1024), 0, st, partials, nparts, (int)(2 * C), dgamma, dbeta);
+  return launch_status();
+}
+
+static int32_t layernorm_bwd_check(const int8_t* dY, const float* SdY, const int8_t* X, const float* SX,
+                                   const float* gamma, const float* mean, const float* rstd, int64_t N, int64_t C,
+                                   int32_t block, int8_t* dX, float* SdX, float* dgamma, float* dbeta) {
   using namespace jf;
   int32_t rc = check_eltwise(X, SX, dX, SdX, N, C, block);
   if (rc != JF_OK) return rc;
@@ -1239,20 +1260,66 @@ extern "C" int32_t jf_layernorm_q_bwd(const int8_t* dY, const float* SdY, const 
   if (!aligned16(dY) || !aligned4(SdY) || !aligned16(gamma) || !aligned4(mean) || !aligned4(rstd) ||
       !aligned4(dgamma) || !aligned4(dbeta))
     return JF_ERR_ALIGN;
+  return JF_OK;
+}
+
+extern "C" int32_t jf_layernorm_q_bwd(const int8_t* dY, const float* SdY, const int8_t* X, const float* SX,
+                                      const float* gamma, const float* mean, const float* rstd, int64_t N, int64_t C,
+                                      int32_t block, int8_t* dX, float* SdX, float* dgamma, float* dbeta, void* ws,
+                                      size_t ws_bytes, void* stream) {
+  int32_t rc = layernorm_bwd_check(dY, SdY, X, SX, gamma, mean, rstd, N, C, block, dX, SdX, dgamma, dbeta);
+  if (rc != JF_OK) return rc;
   const size_t need = jf_workspace_bytes(JF_OP_LAYERNORM_BWD, N, C, 0, block);
   if (!ws || ws_bytes < need) return JF_ERR_WORKSPACE;
-  if (!aligned16(ws)) return JF_ERR_ALIGN;
-  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-  float* partials = static_cast<float*>(ws);
-  const int nparts = (int)ln_bwd_partial_rows(N, C, block);
-  const dim3 grid((unsigned)(C > 2048 ? N / block : nparts));
-  const int nit = (int)((C + 1023) / 1024);
-  // max-abs slots per wave, (row means,) four column-sum rows
-  const size_t lds = C > 2048 ? (16 * (size_t)(C / 32) + 4 * 2 * (size_t)C) * sizeof(float)
-                              : (8 * (size_t)(C / 32) + 2 * (size_t)block + 4 * 2 * (size_t)C) * sizeof(float);
-  JF_LN_DISPATCH(launch_ln_bwd, block, nit, grid, lds, st, dY, SdY, X, SX, gamma, mean, rstd, (int)N, (int)C, dX, SdX, partials);
-  rc = launch_status();
+  if (!jf::aligned16(ws)) return JF_ERR_ALIGN;
+  return layernorm_bwd_launch(dY, SdY, X, SX, gamma, mean, rstd, N, C, block, dX, SdX, dgamma, dbeta,
+                              static_cast<float*>(ws), reinterpret_cast<hipStream_t>(stream));
+}
+
+// ------------------------------------------------------------------------------------------------
+// The entry point that allocates nothing: jf_layernorm_q_bwd with its workspace (the partial rows of
+// dgamma | dbeta) in a static device array instead of a caller-provided buffer.  In host code the array's
+// name is only a handle: its device address is looked up once per device, with that device current, and that
+// pointer is what the kernels receive.  Every GPU holds its own copy of the array until the process ends.
+static __device__ __align__(256) unsigned char scratch[JF_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};  // device address of `scratch` on each device, once looked up
+
+// Device address of the static scratch on the current device (nullptr and *rc = JF_ERR_LAUNCH on failure).
+void* static_scratch(int32_t* rc) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e == hipSuccess && (dev < 0 || dev >= kMaxDevices)) e = hipErrorInvalidDevice;
+  if (e == hipSuccess) {
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {
+      void* p = nullptr;
+      e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+      if (e == hipSuccess && p == nullptr) e = hipErrorInvalidSymbol;
+      if (e == hipSuccess) g_scratch_ptr[dev] = p;
+    }
+    if (e == hipSuccess) return g_scratch_ptr[dev];
+  }
+  jf::g_last_hip_error = (int32_t)e;
+  *rc = JF_ERR_LAUNCH;
+  return nullptr;
+}
+}  // namespace
+
+extern "C" int32_t jf_layernorm_q_bwd_static(const int8_t* dY, const float* SdY, const int8_t* X, const float* SX,
+                                             const float* gamma, const float* mean, const float* rstd, int64_t N,
+                                             int64_t C, int32_t block, int8_t* dX, float* SdX, float* dgamma,
+                                             float* dbeta, void* stream) {
+  int32_t rc = layernorm_bwd_check(dY, SdY, X, SX, gamma, mean, rstd, N, C, block, dX, SdX, dgamma, dbeta);
   if (rc != JF_OK) return rc;
-  hipLaunchKernelGGL(colsum_kernel, dim3((unsigned)((2 * C + 63) / 64)), dim3(1024), 0, st, partials, nparts, (int)(2 * C), dgamma, dbeta);
-  return launch_status();
+  if (jf_workspace_bytes(JF_OP_LAYERNORM_BWD, N, C, 0, block) > (size_t)JF_STATIC_SCRATCH_BYTES) return JF_ERR_WORKSPACE;
+  void* const ptr = static_scratch(&rc);
+  if (ptr == nullptr) return rc;
+  // Nothing in the scratch has to start at zero: every partial row that the second kernel reads is written
+  // in full by the first one of the same call.
+  return layernorm_bwd_launch(dY, SdY, X, SX, gamma, mean, rstd, N, C, block, dX, SdX, dgamma, dbeta,
+                              static_cast<float*>(ptr), reinterpret_cast<hipStream_t>(stream));
 }

@@ -125,3 +125,20 @@ def test_oracle_shares_nothing_with_the_product():
         if f.endswith((".py", ".c", ".h")):
             text = open(os.path.join(odir, f)).read()
             assert "paper_2403_12422_amd" not in text and "jetfire.h" not in text and "csrc" not in text, f
+
+
+def test_static_scratch_entry_point_rejects_what_does_not_fit():
+    """jf_layernorm_q_bwd_static validates like jf_layernorm_q_bwd and refuses problems whose partial rows exceed
+    the static scratch, before anything is looked up or launched."""
+    lib = binding.load_library()
+    call = lambda N, C, block=32, dY=FAKE: lib.jf_layernorm_q_bwd_static(dY, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, N, C, block,
+                                                                       FAKE, FAKE, FAKE, FAKE, None)
+    assert call(64, 64, dY=None) == 1                      # JF_ERR_NULL
+    assert call(48, 64) == 2                               # JF_ERR_SHAPE
+    assert call(64, 8192) == 2                             # LayerNorm rows wider than 4096 columns
+    assert call(64, 64, block=48) == 3                     # JF_ERR_BLOCK
+    assert call(64, 64, dY=ODD) == 4                       # JF_ERR_ALIGN
+    scratch = 8 << 20
+    assert binding.jf_workspace_bytes(binding.JF_OP_LAYERNORM_BWD, 1 << 20, 2048, 0, 32) == scratch     # the largest that fits
+    assert binding.jf_workspace_bytes(binding.JF_OP_LAYERNORM_BWD, 65 * 32, 4096, 0, 32) > scratch
+    assert call(65 * 32, 4096) == 5                        # JF_ERR_WORKSPACE

@@ -438,6 +438,271 @@ __global__ void __launch_bounds__(256) dropout_kernel(const int8_t* __restrict__
 }
 
 // ------------------------------------------------------------------------------------------------
+// Block size 32: the element-wise operators as one WAVE per workgroup.  A wave owns a strip of 32 rows x 128
+// columns -- four quantization blocks side by side.  Lane l = (rsub = l / 8, ch = l % 8) holds the 16-byte chunk ch
+// of rows rsub, rsub + 8, rsub + 16, rsub + 24 of the strip: every load or store instruction of the wave moves
+// eight full 128-byte lines, a lane holds 64 elements of ONE block (columns 32 (ch / 2) .. + 31), so the block's
+// max-abs is a local maximum followed by four cross-lane steps, and nothing is exchanged between waves: no LDS
+// traffic (but the GELU tables), no barrier.  Per element the kernels spend what Alg. 2 needs (unpack, the
+// operator, max-abs, Eq. 1) and little else; the per-lane overhead is paid once per 64 elements.
+struct Strip32 {
+  int ch, rsub;     // chunk column and row of the lane inside an 8-row pass
+  int bi, lc;       // block row of the strip, block columns of the matrix
+  int c0, col;      // first column of the strip, first column of the lane's chunks
+  bool ok;          // the lane's chunks lie inside the matrix (cols % 32 == 0: a block is all in or all out)
+  int64_t base;     // element offset of the lane's chunk in pass 0; pass p adds 8 p cols.  Lanes outside the matrix
+                    // point at the strip's first chunk instead: they load like the others (no branch), share their
+                    // reductions only with each other (whole blocks are in or out), and store nothing.
+  __device__ __forceinline__ Strip32(int cols) {
+    const int lane = threadIdx.x;
+    ch = lane & 7;
+    rsub = lane >> 3;
+    const TileIndex wg = tile_of_workgroup((cols + 127) / 128);
+    c0 = wg.x * 128;
+    bi = wg.y;
+    lc = cols / 32;
+    col = c0 + 16 * ch;
+    ok = col < cols;
+    base = (int64_t)(bi * 32 + rsub) * cols + (ok ? col : c0);
+  }
+  // index of the lane's block in a scale grid (clamped like base)
+  __device__ __forceinline__ int64_t block_index() const { return (int64_t)bi * lc + (ok ? col : c0) / 32; }
+};
+
+// max-abs of 16 values folded into m: eight v_max3_f32 with absolute-value modifiers (the compiler's fmaxf
+// quiets each operand with an extra instruction first)
+__device__ __forceinline__ float amax16(float m, const float (&y)[16]) {
+#pragma unroll
+  for (int e = 0; e < 16; e += 2) asm("v_max3_f32 %0, |%1|, |%2|, %0" : "+v"(m) : "v"(y[e]), "v"(y[e + 1]));
+  return m;
+}
+
+// Block max-abs over the 16 lanes of a strip that share a block column (same ch / 2), then Eq. 1's scale.
+__device__ __forceinline__ void strip32_block_scale(float m, float& scale, double& inv) {
+  m = wave_group_max<56 | 1>(m);
+  block_scale(m, scale, inv);
+}
+
+// One table of GELU (or its derivative) at the 255 values code * sx of a block, indexed by the code byte taken as
+// unsigned: lane l evaluates codes l and l + 64 and, by symmetry, -l and -(l + 64).  Both functions are written in
+// terms of the upper tail Q(a) = Phi(-a), a >= 0 (App. A):
+//   GELU(x) = x Phi(x):  f(a) = a - a Q(a),  f(-a) = -a Q(a);
+//   GELU'(x) = Phi(x) + x phi(x):  f(a) = 1 - Q(a) + a phi(a),  f(-a) = Q(a) - a phi(a),  phi(a) = exp(-a^2/2) / sqrt(2 pi).
+//   Q(a) = t P(t) exp(-a^2/2),  t = 1 / (1 + a / sqrt(8)),  P of degree 8 fitted by weighted least squares on Chebyshev
+//   nodes to erfcx(a / sqrt 2) / (2 t) for 0 <= a <= 13.4 (relative error 5e-8; evaluated in FP32: 4e-7).
+// exp(-a^2/2) = 2^H (1 + r ln 2) with H = fl(-a^2 log2(e)/2) and r the exact remainder (product residuals by FMA),
+// so that the FP32 rounding of an exponent of size a^2 does not cost log2(a^2) bits: Q keeps a relative error of
+// about 1e-6 into the far tail, where a block that lies entirely there takes its scale from.
+template <bool BWD>
+__device__ __forceinline__ void gelu_table_entries(float a, float& pos, float& neg) {
+  const float ac = fminf(a, 40.0f);                       // Q(40) = 0 in FP32; keeps a^2 finite
+  const float t = __builtin_amdgcn_rcpf(__builtin_fmaf(ac, 0.35355339059327373f, 1.0f));
+  float p = -2.9970746985e-02f;
+  p = __builtin_fmaf(p, t, 1.4432375881e-01f);
+  p = __builtin_fmaf(p, t, -2.4760739076e-01f);
+  p = __builtin_fmaf(p, t, 1.4335782902e-01f);
+  p = __builtin_fmaf(p, t, -1.6097390692e-02f);
+  p = __builtin_fmaf(p, t, 1.0243339323e-01f);
+  p = __builtin_fmaf(p, t, 1.2129997806e-01f);
+  p = __builtin_fmaf(p, t, 1.4121892641e-01f);
+  p = __builtin_fmaf(p, t, 1.4104161820e-01f);
+  const float K = -0.72134752044448170f;                  // -log2(e) / 2
+  const float aa = ac * ac;
+  const float lo = __builtin_fmaf(ac, ac, -aa);           // a^2 = aa + lo exactly
+  const float H = aa * K;
+  const float r = __builtin_fmaf(lo, K, __builtin_fmaf(aa, K, -H));
+  const float ez = __builtin_amdgcn_exp2f(H) * __builtin_fmaf(r, 0.6931471805599453f, 1.0f);   // exp(-a^2/2)
+  const float q = (t * p) * ez;
+  if (BWD) {
+    const float s = (a * 0.39894228040143268f) * ez;      // a phi(a)
+    pos = (1.0f - q) + s;
+    neg = q - s;
+  } else {
+    const float aq = a * q;
+    pos = a - aq;
+    neg = 0.0f - aq;
+  }
+}
+
+template <bool BWD>
+__device__ __forceinline__ void gelu_build_table(float* tab, float sx, int lane) {
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const int i = lane + 64 * h;
+    float pos, neg;
+    gelu_table_entries<BWD>((float)i * sx, pos, neg);
+    // code 0: GELU(0) = 0 comes out exactly; GELU'(0) = 1/2 is set, because the fit is only good to 4e-7 there and a
+    // derivative of 0.49999997 would push every halved gradient code off its rounding tie.  Entry 128 (code -128,
+    // which no quantizer output holds) is 0.
+    tab[i] = (BWD && i == 0) ? 0.5f : pos;
+    tab[i == 0 ? 128 : 256 - i] = i == 0 ? 0.0f : neg;
+  }
+}
+
+template <bool BWD>
+__global__ void __launch_bounds__(64) gelu_strip32_kernel(const int8_t* __restrict__ X, const float* __restrict__ SX,
+                                                          const int8_t* __restrict__ G, const float* __restrict__ SG,
+                                                          int rows, int cols, int8_t* __restrict__ Y, float* __restrict__ SY) {
+  __shared__ float s_tab[4][256];
+  const Strip32 t(cols);
+  const int64_t pass = (int64_t)8 * cols;
+  // the codes are requested first: their latency runs beside the table build
+  uint4 px[4], pg[BWD ? 4 : 1];
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    px[p] = *reinterpret_cast<const uint4*>(X + t.base + p * pass);
+    if (BWD) pg[p] = *reinterpret_cast<const uint4*>(G + t.base + p * pass);
+  }
+  // the strip's block scales are the same for all lanes: scalar loads (the grids are not written by this kernel)
+  typedef const __attribute__((address_space(4))) float* const_f32_ptr;
+  const const_f32_ptr sx_row = (const_f32_ptr)SX + (int64_t)t.bi * t.lc + t.c0 / 32;
+  const int nblk = min(4, t.lc - t.c0 / 32);
+#pragma unroll
+  for (int k = 0; k < 4; ++k)
+    if (k < nblk) gelu_build_table<BWD>(s_tab[k], sx_row[k], threadIdx.x);
+  // The tables are written and read by this wave only; LDS serves a wave's accesses in program order, and the
+  // fences keep the compiler from moving the lookups above the writes.
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+  float y[4][16];
+  float m = 0.0f;
+  const float* tab = s_tab[t.ch >> 1];   // lanes outside the matrix may read a table nobody built: see Strip32::base
+  float sg = 0.0f, sg128 = 0.0f;
+  if (BWD) {
+    sg = SG[t.block_index()];
+    sg128 = -128.0f * sg;
+  }
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    const uint32_t w[4] = {px[p].x, px[p].y, px[p].z, px[p].w};
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+      y[p][4 * d + 0] = tab[w[d] & 0xffu];
+      y[p][4 * d + 1] = tab[(w[d] >> 8) & 0xffu];
+      y[p][4 * d + 2] = tab[(w[d] >> 16) & 0xffu];
+      y[p][4 * d + 3] = tab[w[d] >> 24];
+    }
+    if (BWD) {
+      float ug[16];
+      unpack16_biased(pg[p], ug);
+#pragma unroll
+      for (int e = 0; e < 16; ++e) y[p][e] = __builtin_fmaf(ug[e], sg, sg128) * y[p][e];
+    }
+    m = amax16(m, y[p]);
+  }
+  float scale;
+  double inv;
+  strip32_block_scale(m, scale, inv);
+  if (!t.ok) return;
+  if ((threadIdx.x & 57) == 0) SY[t.block_index()] = scale;
+#pragma unroll
+  for (int p = 0; p < 4; ++p) *reinterpret_cast<uint4*>(Y + t.base + p * pass) = quantize16(y[p], inv);
+}
+
+// Add (App. A) at block size 32, optionally with the row partials of App. A's LayerNorm paragraph (PARTIALS).
+template <bool PARTIALS>
+__global__ void __launch_bounds__(64) add_strip32_kernel(const int8_t* __restrict__ X1, const float* __restrict__ S1,
+                                                         const int8_t* __restrict__ X2, const float* __restrict__ S2,
+                                                         int rows, int cols, int8_t* __restrict__ Y, float* __restrict__ SY,
+                                                         float* __restrict__ row_mean, float* __restrict__ row_sumsq) {
+  const Strip32 t(cols);
+  const int64_t pass = (int64_t)8 * cols;
+  float y[4][16];
+  float m = 0.0f;
+  uint4 p1[4], p2[4];
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    p1[p] = *reinterpret_cast<const uint4*>(X1 + t.base + p * pass);
+    p2[p] = *reinterpret_cast<const uint4*>(X2 + t.base + p * pass);
+  }
+  const float s1 = S1[t.block_index()], s2 = S2[t.block_index()];
+  const float k = -128.0f * (s1 + s2);  // the unpacked codes carry +128
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    float u1[16], u2[16];
+    unpack16_biased(p1[p], u1);
+    unpack16_biased(p2[p], u2);
+#pragma unroll
+    for (int e = 0; e < 16; ++e) y[p][e] = __builtin_fmaf(u1[e], s1, __builtin_fmaf(u2[e], s2, k));
+    m = amax16(m, y[p]);
+    if (PARTIALS) {  // per row and block: mean and sum of squares over the block's 32 columns = two neighbouring lanes
+      float ps = 0.0f, pq = 0.0f;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        ps += y[p][e];
+        pq = __builtin_fmaf(y[p][e], y[p][e], pq);
+      }
+      ps = wave_group_sum<1>(ps);
+      pq = wave_group_sum<1>(pq);
+      if (t.ok && (t.ch & 1) == 0) {
+        const int64_t o = (int64_t)(t.bi * 32 + t.rsub + 8 * p) * t.lc + t.col / 32;
+        row_mean[o] = ps * (1.0f / 32.0f);
+        row_sumsq[o] = pq;
+      }
+    }
+  }
+  float scale;
+  double inv;
+  strip32_block_scale(m, scale, inv);
+  if (!t.ok) return;
+  if ((threadIdx.x & 57) == 0) SY[t.block_index()] = scale;
+#pragma unroll
+  for (int p = 0; p < 4; ++p) *reinterpret_cast<uint4*>(Y + t.base + p * pass) = quantize16(y[p], inv);
+}
+
+// The four keep bits of one packed dword of codes -> 0xff / 0x00 per byte: the multiplication puts bit j of the
+// nibble at bit 8 j (and copies elsewhere, which the mask removes), times 255 fills the byte.
+__device__ __forceinline__ uint32_t keep_bytes(uint32_t nibble) {
+  const uint32_t ones = (nibble * 0x00204081u) & 0x01010101u;
+  uint32_t full;  // ones * 255 as shift and subtract (the compiler would make it a slow 32-bit multiplication)
+  asm("v_lshlrev_b32 %0, 8, %1\n\tv_sub_u32 %0, %0, %1" : "=&v"(full) : "v"(ones));
+  return full;
+}
+
+// Dropout (App. A) at block size 32: dropped codes are cleared in the packed dwords (a code of 0 dequantizes to
+// exactly 0), so the mask costs a few integer instructions per four elements and none per element.
+__global__ void __launch_bounds__(64) dropout_strip32_kernel(const int8_t* __restrict__ X, const float* __restrict__ SX,
+                                                             const uint8_t* __restrict__ mask, float keep_scale, int rows,
+                                                             int cols, int8_t* __restrict__ Y, float* __restrict__ SY) {
+  const Strip32 t(cols);
+  const int64_t pass = (int64_t)8 * cols;
+  float y[4][16];
+  float m = 0.0f;
+  uint4 px[4];
+  uint32_t bits[4];
+  const int64_t mbase = t.base >> 3;   // row * (cols / 8) + column / 8: cols is a multiple of 32, the column of 16
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    px[p] = *reinterpret_cast<const uint4*>(X + t.base + p * pass);
+    bits[p] = *reinterpret_cast<const uint16_t*>(mask + mbase + (int64_t)p * cols);   // 8 rows further: 8 * cols / 8 bytes
+  }
+  const float k = SX[t.block_index()] * keep_scale;
+  const float k128 = -128.0f * k;  // the unpacked codes carry +128
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    uint4 c = px[p];
+    c.x &= keep_bytes(bits[p] & 15u);
+    c.y &= keep_bytes((bits[p] >> 4) & 15u);
+    c.z &= keep_bytes((bits[p] >> 8) & 15u);
+    c.w &= keep_bytes(bits[p] >> 12);
+    float u[16];
+    unpack16_biased(c, u);
+#pragma unroll
+    for (int e = 0; e < 16; ++e) y[p][e] = __builtin_fmaf(u[e], k, k128);
+    m = amax16(m, y[p]);
+  }
+  float scale;
+  double inv;
+  strip32_block_scale(m, scale, inv);
+  if (!t.ok) return;
+  if ((threadIdx.x & 57) == 0) SY[t.block_index()] = scale;
+#pragma unroll
+  for (int p = 0; p < 4; ++p) *reinterpret_cast<uint4*>(Y + t.base + p * pass) = quantize16(y[p], inv);
+}
+
+// ------------------------------------------------------------------------------------------------
 // LayerNorm.  One workgroup of four waves owns B rows and all C columns; wave w owns rows
 // [w*B/4, (w+1)*B/4).  Lane l of a wave owns the 16-byte chunks l, l+64, ... of each of its rows, so a
 // row is read as contiguous 1 KB runs and per-column quantities (gamma, beta, column sums) stay in
@@ -1083,19 +1348,18 @@ static void launch_gelu_cfg(const int8_t* X, const float* SX, const int8_t* G, c
 template <bool BWD>
 static void launch_gelu(int block, const int8_t* X, const float* SX, const int8_t* G, const float* SG, int rows,
                         int cols, int8_t* Y, float* SY, hipStream_t st) {
-  // B = 32 / 64: one block per wave while the tensors are small enough to sit in the last-level cache (measured
-  // 10-14 % faster at 4096 x 3072; its 32- / 64-byte row pieces cost a third of the bandwidth once the data
-  // comes from HBM: crossover near 40 M elements at B = 32 and 100 M at B = 64).  Beyond that one block per
-  // workgroup column, in workgroups of 256 columns (such tensors take thousands of them; 6-7 % faster from HBM
-  // than 128 columns).  At B = 128 a lane already holds four 8-row passes of a 128-column workgroup.
+  // B = 32: one wave per workgroup and strip of 32 x 128 at every size.  B = 64: one block per wave while the
+  // tensors are small enough to sit in the last-level cache (its 64-byte row pieces cost a third of the
+  // bandwidth once the data comes from HBM: crossover near 100 M elements), beyond that one block per workgroup
+  // column, in workgroups of 256 columns.  At B = 128 a lane already holds four 8-row passes of a 128-column workgroup.
   const int64_t n = (int64_t)rows * cols;
   if (block == 128) launch_gelu_cfg<BWD, 128, 1>(X, SX, G, SG, rows, cols, Y, SY, st);
   else if (block == 64) {
     if (n <= (int64_t(64) << 20)) launch_gelu_wave<BWD, 64>(X, SX, G, SG, rows, cols, Y, SY, st);
     else launch_gelu_cfg<BWD, 64, 2>(X, SX, G, SG, rows, cols, Y, SY, st);
   } else {
-    if (n <= (int64_t(24) << 20)) launch_gelu_wave<BWD, 32>(X, SX, G, SG, rows, cols, Y, SY, st);
-    else launch_gelu_cfg<BWD, 32, 2>(X, SX, G, SG, rows, cols, Y, SY, st);
+    hipLaunchKernelGGL((gelu_strip32_kernel<BWD>), dim3(tile_grid((cols + 127) / 128, rows / 32)), dim3(64), 0, st, X, SX, G, SG,
+                       rows, cols, Y, SY);
   }
 }
 
@@ -1206,7 +1470,9 @@ extern "C" int32_t jf_dropout_q(const int8_t* X, const float* SX, const uint8_t*
   const dim3 grid(tile_grid((C + 127) / 128, N / block));
   const float keep_scale = (float)(1.0 / (1.0 - (double)p));
   const int rows = (int)N, cols = (int)C;
-  if (block == 32) hipLaunchKernelGGL((dropout_kernel<32>), grid, dim3(256), 0, st, X, SX, mask_bits, keep_scale, rows, cols, Y, SY);
+  if (block == 32)
+    hipLaunchKernelGGL(dropout_strip32_kernel, dim3(tile_grid((C + 127) / 128, N / 32)), dim3(64), 0, st, X, SX, mask_bits,
+                       keep_scale, rows, cols, Y, SY);
   else if (block == 64) hipLaunchKernelGGL((dropout_kernel<64>), grid, dim3(256), 0, st, X, SX, mask_bits, keep_scale, rows, cols, Y, SY);
   else hipLaunchKernelGGL((dropout_kernel<128>), grid, dim3(256), 0, st, X, SX, mask_bits, keep_scale, rows, cols, Y, SY);
   return launch_status();
@@ -1223,8 +1489,11 @@ extern "C" int32_t jf_add_q(const int8_t* X1, const float* S1, const int8_t* X2,
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   const dim3 grid(tile_grid((C + 127) / 128, N / block));
   const int rows = (int)N, cols = (int)C;
-  if (block == 32) hipLaunchKernelGGL((add_kernel<32>), grid, dim3(256), 0, st, X1, S1, X2, S2, rows, cols, Y, SY, row_mean, row_sumsq);
-  else if (block == 64) hipLaunchKernelGGL((add_kernel<64>), grid, dim3(256), 0, st, X1, S1, X2, S2, rows, cols, Y, SY, row_mean, row_sumsq);
+  if (block == 32) {
+    const dim3 strips(tile_grid((C + 127) / 128, N / 32));
+    if (row_mean) hipLaunchKernelGGL((add_strip32_kernel<true>), strips, dim3(64), 0, st, X1, S1, X2, S2, rows, cols, Y, SY, row_mean, row_sumsq);
+    else hipLaunchKernelGGL((add_strip32_kernel<false>), strips, dim3(64), 0, st, X1, S1, X2, S2, rows, cols, Y, SY, row_mean, row_sumsq);
+  } else if (block == 64) hipLaunchKernelGGL((add_kernel<64>), grid, dim3(256), 0, st, X1, S1, X2, S2, rows, cols, Y, SY, row_mean, row_sumsq);
   else hipLaunchKernelGGL((add_kernel<128>), grid, dim3(256), 0, st, X1, S1, X2, S2, rows, cols, Y, SY, row_mean, row_sumsq);
   return launch_status();
 }

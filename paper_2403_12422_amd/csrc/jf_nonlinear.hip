@@ -7,6 +7,7 @@
 //     indexed by its code byte -- the dequantize step of Alg. 2 and the erf evaluation collapse into it;
 //   * LayerNorm: row sums come from exact integer dot products of the codes (v_dot4), scaled per block,
 //     which is the row-partials scheme of App. A applied to the INT8 input itself.
+#include <algorithm>
 #include <mutex>
 
 #include "jf_common.hpp"
@@ -1300,6 +1301,320 @@ __global__ void __launch_bounds__(1024) layernorm_bwd_wide_kernel(const int8_t* 
   }
 }
 
+// ------------------------------------------------------------------------------------------------
+// LayerNorm at block size 32.  Where whole rows are needed a workgroup owns 32 of them and is made of strip waves:
+// wave w holds the 32 x 128 strip w of those rows with the lane mapping of Strip32 (C / 128 waves, at most 16).  What
+// needs a whole row (the row sums) is reduced over the 8 chunk lanes of a row inside each wave (three DPP steps)
+// and over the strips through a few hundred bytes of LDS, in a fixed order; what belongs to a block (max-abs,
+// scale) or to a column (gamma, beta, the column sums of the backward pass) never leaves its wave.
+// WMAX = most waves the instance is compiled for (the register budget follows from it).
+struct RowStrips32 {
+  int ch, rsub, wave, nstrips;
+  int lc, col;
+  bool ok;
+  __device__ __forceinline__ RowStrips32(int cols) {
+    const int lane = threadIdx.x & 63;
+    ch = lane & 7;
+    rsub = lane >> 3;
+    wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    nstrips = blockDim.x >> 6;
+    lc = cols / 32;
+    // rows wider than 16 strips are shared by the workgroups blockIdx.y = 0, 1, ...: 2048 columns each
+    const int c0 = (blockIdx.y * 16 + wave) * 128, c = c0 + 16 * ch;
+    ok = c < cols;
+    col = ok ? c : min(c0, cols - 32);   // lanes outside the matrix point at a valid chunk instead, see Strip32
+  }
+  // element offset of the lane's chunk of row rsub of block row bi; pass p adds 8 p cols
+  __device__ __forceinline__ int64_t base(int bi, int cols) const { return (int64_t)(bi * 32 + rsub) * cols + col; }
+  __device__ __forceinline__ int64_t block_index(int bi) const { return (int64_t)bi * lc + col / 32; }
+};
+
+// Row statistics of LayerNorm from the codes (App. A: "mean and sum of squares", here of the INT8 input itself), for
+// rows of any width: the workgroup's waves share the strips of its 32 rows (wave w takes strips w, w + waves, ...).
+// Per 16-code chunk the sum and the sum of squares of the codes are exact integers (v_dot4); times the block scale,
+// in double, they are the chunk's share of the row's sum and sum of squares.  The shares are added over a lane's
+// strips, over the 8 chunk lanes of a row (three DPP steps) and over the waves through LDS, in a fixed order.  The
+// normalisation itself is layernorm_apply_strip32_kernel, an element-wise operator on strips.
+__global__ void __launch_bounds__(1024) layernorm_row_stats_strips32_kernel(const int8_t* __restrict__ X, const float* __restrict__ SX,
+                                                                           float eps, int rows, int cols,
+                                                                           float* __restrict__ mean_out, float* __restrict__ rstd_out) {
+  __shared__ double s_row[16][32][2];
+  const int lane = threadIdx.x & 63, ch = lane & 7, rsub = lane >> 3;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), nwaves = blockDim.x >> 6;
+  const int bi = blockIdx.x, lc = cols / 32;
+  const int64_t pass = (int64_t)8 * cols;
+  double cs[4] = {0.0, 0.0, 0.0, 0.0}, cq[4] = {0.0, 0.0, 0.0, 0.0};
+  for (int c0 = wave * 128; c0 < cols; c0 += nwaves * 128) {
+    const bool ok = c0 + 16 * ch < cols;
+    const int col = ok ? c0 + 16 * ch : c0;   // lanes outside the matrix read the strip's first chunk and add nothing
+    const int64_t base = (int64_t)(bi * 32 + rsub) * cols + col;
+    uint4 px[4];
+#pragma unroll
+    for (int p = 0; p < 4; ++p) px[p] = *reinterpret_cast<const uint4*>(X + base + p * pass);
+    const double sd = ok ? (double)SX[(int64_t)bi * lc + col / 32] : 0.0;
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      int s1, s2;
+      chunk_moments(px[p], s1, s2);
+      cs[p] += sd * (double)s1;
+      cq[p] += sd * sd * (double)s2;
+    }
+  }
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    const double s = wave_group_sum_f64<7>(cs[p]), q = wave_group_sum_f64<7>(cq[p]);
+    if (ch == 0) {
+      s_row[wave][rsub + 8 * p][0] = s;
+      s_row[wave][rsub + 8 * p][1] = q;
+    }
+  }
+  __syncthreads();
+  if (threadIdx.x < 32) {   // row threadIdx.x of the block: the waves in a fixed order
+    double s = 0.0, q = 0.0;
+    for (int w = 0; w < nwaves; ++w) {
+      s += s_row[w][threadIdx.x][0];
+      q += s_row[w][threadIdx.x][1];
+    }
+    const double inv_cols = 1.0 / (double)cols, mud = s * inv_cols;
+    const float var = fmaxf((float)(q * inv_cols - mud * mud), 0.0f);
+    // reciprocal square root: hardware approximation refined by one Newton step (relative error ~1e-7)
+    const float ve = var + eps;
+    float rs = __builtin_amdgcn_rsqf(ve);
+    rs = rs * __builtin_fmaf(-0.5f * ve * rs, rs, 1.5f);
+    mean_out[bi * 32 + threadIdx.x] = (float)mud;
+    rstd_out[bi * 32 + threadIdx.x] = rs;
+  }
+}
+
+// LayerNorm backward at block size 32, in two kernels.  With ghat = g gamma and xhat = (x - mean) rstd,
+//   dx = rstd (ghat - mean_C(ghat) - xhat mean_C(ghat xhat)),  dgamma = sum_N g xhat,  dbeta = sum_N g.
+// Everything that needs a whole row or a whole column is a sum, and sums are cheap to hand over: the first kernel
+// reads g and x once and leaves the two row means per row and one row of dgamma | dbeta partial sums per workgroup
+// in the workspace; the second one is an element-wise operator on 32 x 128 strips like GELU backward.  (One kernel
+// that does both has to keep dx, the codes and the column sums in registers at once: about 250, which leaves a
+// compute unit with a single workgroup and nothing to overlap its memory latency with.)
+//
+// First kernel: the workgroup of strip waves described above walks over the row blocks blockIdx.x, blockIdx.x +
+// gridDim.x, ... (four waves per SIMD: another workgroup's loads run beside this one's arithmetic).  The row sums go over the chunk lanes, then over the
+// strips through LDS (two copies used by alternate row blocks: one barrier per block); the running column sums of
+// g xhat and g stay in registers over all row blocks -- a lane always holds the same 16 columns -- and are added
+// over the 8 row lanes of the wave at the end (every wave owns its own 128 columns of the partial row).  All orders
+// are fixed: results are bit-stable from run to run.
+template <int WMAX>
+__global__ void __launch_bounds__(64 * WMAX) __attribute__((amdgpu_waves_per_eu(4))) layernorm_bwd_sums_strips32_kernel(
+    const int8_t* __restrict__ G, const float* __restrict__ SG, const int8_t* __restrict__ X, const float* __restrict__ SX,
+    const float* __restrict__ gamma, const float* __restrict__ mean_in, const float* __restrict__ rstd_in, int rows,
+    int cols, float* __restrict__ row_means, float* __restrict__ partials) {
+  __shared__ float s_row[2][WMAX][32][2];   // [row block parity][strip][row]: sums of ghat and of ghat xhat
+  const RowStrips32 t(cols);
+  const int64_t pass = (int64_t)8 * cols;
+  const int nblocks = rows / 32;
+  const float inv_cols = 1.0f / (float)cols;
+  float gm[16], cgs[16], cbs[16];
+  load16f(gamma + t.col, gm);
+#pragma unroll
+  for (int e = 0; e < 16; ++e) cgs[e] = cbs[e] = 0.0f;
+
+  int parity = 0;
+  for (int bi = blockIdx.x; bi < nblocks; bi += gridDim.x, parity ^= 1) {
+    const int64_t base = t.base(bi, cols);
+    uint4 px[4], pg[4];
+    float mu[4], rs[4];
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      px[p] = *reinterpret_cast<const uint4*>(X + base + p * pass);
+      pg[p] = *reinterpret_cast<const uint4*>(G + base + p * pass);
+      mu[p] = mean_in[bi * 32 + t.rsub + 8 * p];
+      rs[p] = rstd_in[bi * 32 + t.rsub + 8 * p];
+    }
+    const float sx = SX[t.block_index(bi)];
+    const float sg = t.ok ? SG[t.block_index(bi)] : 0.0f;   // lanes outside the matrix add nothing to the sums
+    const float g128 = -128.0f * sg;
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      float ux[16], ug[16];
+      unpack16_biased(px[p], ux);
+      unpack16_biased(pg[p], ug);
+      const float kx = sx * rs[p], cx0 = __builtin_fmaf(-128.0f, kx, -mu[p] * rs[p]);
+      float m1 = 0.0f, m2 = 0.0f;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const float xh = __builtin_fmaf(ux[e], kx, cx0);
+        const float gv = __builtin_fmaf(ug[e], sg, g128);
+        const float gh = gv * gm[e];
+        m1 += gh;
+        m2 = __builtin_fmaf(gh, xh, m2);
+        // the column sums are updated in place, in program order (left to itself the compiler parks them in
+        // scratch memory and keeps the operands of sixteen deferred updates alive instead)
+        asm volatile("v_fmac_f32 %0, %1, %2" : "+v"(cgs[e]) : "v"(gv), "v"(xh));
+        asm volatile("v_add_f32 %0, %0, %1" : "+v"(cbs[e]) : "v"(gv));
+      }
+      m1 = wave_group_sum<7>(m1);
+      m2 = wave_group_sum<7>(m2);
+      if (t.ch == 0) {
+        s_row[parity][t.wave][t.rsub + 8 * p][0] = m1;
+        s_row[parity][t.wave][t.rsub + 8 * p][1] = m2;
+      }
+      __builtin_amdgcn_sched_barrier(0);   // one pass at a time: interleaved passes keep their unpacked values live together
+    }
+    __syncthreads();
+    if (threadIdx.x < 32) {   // row threadIdx.x of the block: the strips in a fixed order
+      float q1 = 0.0f, q2 = 0.0f;
+      for (int w = 0; w < t.nstrips; ++w) {
+        q1 += s_row[parity][w][threadIdx.x][0];
+        q2 += s_row[parity][w][threadIdx.x][1];
+      }
+      // (the share of this workgroup's column range; the second kernel adds the ranges)
+      *reinterpret_cast<float2*>(row_means + 2 * ((int64_t)blockIdx.y * rows + bi * 32 + threadIdx.x)) =
+          make_float2(q1 * inv_cols, q2 * inv_cols);
+    }
+  }
+
+  // column sums over the 8 row lanes of the wave; the lanes of row 0 write the wave's 128 columns of the partial row
+#pragma unroll
+  for (int e = 0; e < 16; ++e) {
+    cgs[e] = wave_group_sum<56>(cgs[e]);
+    cbs[e] = wave_group_sum<56>(cbs[e]);
+  }
+  if (t.ok && t.rsub == 0) {
+    float* dst = partials + (int64_t)blockIdx.x * 2 * cols + t.col;
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+      *reinterpret_cast<float4*>(dst + 4 * d) = make_float4(cgs[4 * d], cgs[4 * d + 1], cgs[4 * d + 2], cgs[4 * d + 3]);
+      *reinterpret_cast<float4*>(dst + cols + 4 * d) = make_float4(cbs[4 * d], cbs[4 * d + 1], cbs[4 * d + 2], cbs[4 * d + 3]);
+    }
+  }
+}
+
+// Second kernel: dx on 32 x 128 strips, one wave each, from the row means q1 = mean_C(ghat), q2 = mean_C(ghat xhat)
+// that the first kernel left (one share per range of 2048 columns): dx = ug a_c + ux b + d with per-row b = -rstd q2 sx rstd, d and per-column
+// a_c = rstd sg gamma_c (u = code + 128), then Eq. 1.  Rows may be of any width.
+__global__ void __launch_bounds__(64) layernorm_bwd_apply_strip32_kernel(
+    const int8_t* __restrict__ G, const float* __restrict__ SG, const int8_t* __restrict__ X, const float* __restrict__ SX,
+    const float* __restrict__ gamma, const float* __restrict__ mean_in, const float* __restrict__ rstd_in,
+    const float* __restrict__ row_means, int ranges, int rows, int cols, int8_t* __restrict__ dX, float* __restrict__ SdX) {
+  const Strip32 t(cols);
+  const int64_t pass = (int64_t)8 * cols;
+  uint4 px[4], pg[4];
+  float mu[4], rs[4];
+  float2 q[4];
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    px[p] = *reinterpret_cast<const uint4*>(X + t.base + p * pass);
+    pg[p] = *reinterpret_cast<const uint4*>(G + t.base + p * pass);
+    const int row = t.bi * 32 + t.rsub + 8 * p;
+    mu[p] = mean_in[row];
+    rs[p] = rstd_in[row];
+    q[p] = *reinterpret_cast<const float2*>(row_means + 2 * (int64_t)row);
+    for (int cr = 1; cr < ranges; ++cr) {   // rows wider than 2048 columns: the column ranges in a fixed order
+      const float2 part = *reinterpret_cast<const float2*>(row_means + 2 * ((int64_t)cr * rows + row));
+      q[p].x += part.x;
+      q[p].y += part.y;
+    }
+  }
+  const float sx = SX[t.block_index()], sg = SG[t.block_index()];
+  float gm[16];
+  load16f(gamma + (t.ok ? t.col : t.c0), gm);
+  float y[4][16];
+  float m = 0.0f;
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    float ux[16], ug[16];
+    unpack16_biased(px[p], ux);
+    unpack16_biased(pg[p], ug);
+    const float kx = sx * rs[p], cx0 = __builtin_fmaf(-128.0f, kx, -mu[p] * rs[p]);
+    const float kxm = -rs[p] * q[p].y * kx, krow = -rs[p] * __builtin_fmaf(cx0, q[p].y, q[p].x);
+    const float rsg = rs[p] * sg;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      const float a = rsg * gm[e];
+      const float k = __builtin_fmaf(a, -128.0f, krow);
+      y[p][e] = __builtin_fmaf(ux[e], kxm, __builtin_fmaf(ug[e], a, k));
+    }
+    m = amax16(m, y[p]);
+  }
+  float scale;
+  double inv;
+  strip32_block_scale(m, scale, inv);
+  if (!t.ok) return;
+  if ((threadIdx.x & 57) == 0) SdX[t.block_index()] = scale;
+#pragma unroll
+  for (int p = 0; p < 4; ++p) *reinterpret_cast<uint4*>(dX + t.base + p * pass) = quantize16(y[p], inv);
+}
+
+// Row statistics of LayerNorm from the row partials that the preceding Add wrote (App. A, LayerNorm paragraph):
+//   mean_i = (1 / L_C) sum_j row_mean[i][j],  var_i = max((1 / C) sum_j row_sumsq[i][j] - mean_i^2, 0),
+// summed in double in a fixed order; rstd as the hardware reciprocal square root plus one Newton step.  A group of
+// 8 lanes owns a row: the lanes read the row's partials as consecutive floats (a wave reads eight rows, which lie
+// back to back in memory) and add their shares with three butterfly steps.
+__global__ void __launch_bounds__(256) row_stats_from_partials_kernel(const float* __restrict__ row_mean,
+                                                                       const float* __restrict__ row_sumsq, float eps,
+                                                                       int rows, int lc, int cols,
+                                                                       float* __restrict__ mean_out, float* __restrict__ rstd_out) {
+  const int sub = threadIdx.x & 7;
+  const int row = min(blockIdx.x * 32 + (threadIdx.x >> 3), rows - 1);   // surplus groups repeat the last row
+  const float* pm = row_mean + (int64_t)row * lc;
+  const float* pq = row_sumsq + (int64_t)row * lc;
+  double s = 0.0, q = 0.0;
+  for (int j = sub; j < lc; j += 8) {
+    s += (double)pm[j];
+    q += (double)pq[j];
+  }
+  s = wave_group_sum_f64<7>(s);
+  q = wave_group_sum_f64<7>(q);
+  const double mu = s / (double)lc;
+  const float var = fmaxf((float)(q / (double)cols - mu * mu), 0.0f);
+  const float ve = var + eps;
+  float rs = __builtin_amdgcn_rsqf(ve);
+  rs = rs * __builtin_fmaf(-0.5f * ve * rs, rs, 1.5f);
+  if (sub == 0) {
+    mean_out[row] = (float)mu;
+    rstd_out[row] = rs;
+  }
+}
+
+// LayerNorm at block size 32 from given row statistics (App. A: the operator "directly accesses" mean and rstd):
+// y = (x - mean) rstd gamma + beta on 32 x 128 strips, one wave each, like the other element-wise operators --
+// no workgroup needs a whole row, so rows may be of any width.
+__global__ void __launch_bounds__(64) layernorm_apply_strip32_kernel(const int8_t* __restrict__ X, const float* __restrict__ SX,
+                                                                     const float* __restrict__ gamma, const float* __restrict__ beta,
+                                                                     const float* __restrict__ mean_in, const float* __restrict__ rstd_in,
+                                                                     int rows, int cols, int8_t* __restrict__ Y, float* __restrict__ SY) {
+  const Strip32 t(cols);
+  const int64_t pass = (int64_t)8 * cols;
+  uint4 px[4];
+  float mu[4], rs[4];
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    px[p] = *reinterpret_cast<const uint4*>(X + t.base + p * pass);
+    mu[p] = mean_in[t.bi * 32 + t.rsub + 8 * p];
+    rs[p] = rstd_in[t.bi * 32 + t.rsub + 8 * p];
+  }
+  const float sx = SX[t.block_index()];
+  float gm[16], bt[16];
+  const int gcol = t.ok ? t.col : t.c0;
+  load16f(gamma + gcol, gm);
+  load16f(beta + gcol, bt);
+  float y[4][16];
+  float m = 0.0f;
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    float u[16];
+    unpack16_biased(px[p], u);
+    const float k1 = sx * rs[p], kb = __builtin_fmaf(-128.0f, k1, -mu[p] * rs[p]);
+#pragma unroll
+    for (int e = 0; e < 16; ++e) y[p][e] = __builtin_fmaf(__builtin_fmaf(u[e], k1, kb), gm[e], bt[e]);
+    m = amax16(m, y[p]);
+  }
+  float scale;
+  double inv;
+  strip32_block_scale(m, scale, inv);
+  if (!t.ok) return;
+  if ((threadIdx.x & 57) == 0) SY[t.block_index()] = scale;
+#pragma unroll
+  for (int p = 0; p < 4; ++p) *reinterpret_cast<uint4*>(Y + t.base + p * pass) = quantize16(y[p], inv);
+}
+
 // dgamma / dbeta: sum the per-wave partial rows in a fixed order (bit-stable from run to run).  A workgroup
 // of 16 waves owns 64 columns of the 2*C wide partial matrix; wave w sums rows w, w+16, w+32, ... (eight
 // independent chains keep loads in flight), and wave 0 adds the 16 results in wave order.
@@ -1425,6 +1740,14 @@ extern "C" int32_t jf_gelu_q_bwd(const int8_t* dY, const float* SdY, const int8_
   return launch_status();
 }
 
+template <typename... Args>
+static void launch_ln_bwd_sums_strips32(int64_t C, dim3 grid, hipStream_t st, Args... args) {
+  const int ns = (int)std::min<int64_t>(16, (C + 127) / 128);   // waves; the last column range may use fewer of them
+  if (ns <= 4) hipLaunchKernelGGL((jf::layernorm_bwd_sums_strips32_kernel<4>), grid, dim3(64 * ns), 0, st, args...);
+  else if (ns <= 8) hipLaunchKernelGGL((jf::layernorm_bwd_sums_strips32_kernel<8>), grid, dim3(64 * ns), 0, st, args...);
+  else hipLaunchKernelGGL((jf::layernorm_bwd_sums_strips32_kernel<16>), grid, dim3(64 * ns), 0, st, args...);
+}
+
 static int32_t layernorm_fwd(const int8_t* X, const float* SX, const float* row_mean, const float* row_sumsq,
                              const float* gamma, const float* beta, float eps, int64_t N, int64_t C, int32_t block,
                              int8_t* Y, float* SY, float* mean, float* rstd, void* stream) {
@@ -1432,9 +1755,27 @@ static int32_t layernorm_fwd(const int8_t* X, const float* SX, const float* row_
   int32_t rc = check_eltwise(X, SX, Y, SY, N, C, block);
   if (rc != JF_OK) return rc;
   if (!gamma || !beta || !mean || !rstd) return JF_ERR_NULL;
-  if (C > kLayerNormMaxC) return JF_ERR_SHAPE;
+  // Block size 32: a statistics kernel (from the Add's partials, or from the codes) and the normalisation on
+  // 32 x 128 strips; no workgroup holds a whole row in registers, so rows may be of any width.
+  const bool strips = block == 32;
+  if (C > kLayerNormMaxC && !strips) return JF_ERR_SHAPE;
   if (!aligned16(gamma) || !aligned16(beta) || !aligned4(mean) || !aligned4(rstd)) return JF_ERR_ALIGN;
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  if (strips) {
+    if (row_mean != nullptr) {
+      hipLaunchKernelGGL(row_stats_from_partials_kernel, dim3((unsigned)((N + 31) / 32)), dim3(256), 0, st, row_mean, row_sumsq,
+                         eps, (int)N, (int)(C / 32), (int)C, mean, rstd);
+    } else {
+      const int waves = (int)std::min<int64_t>(16, (C + 127) / 128);
+      hipLaunchKernelGGL(layernorm_row_stats_strips32_kernel, dim3((unsigned)(N / 32)), dim3(64 * waves), 0, st, X, SX, eps, (int)N,
+                         (int)C, mean, rstd);
+    }
+    rc = launch_status();
+    if (rc != JF_OK) return rc;
+    hipLaunchKernelGGL(layernorm_apply_strip32_kernel, dim3(tile_grid((C + 127) / 128, N / 32)), dim3(64), 0, st, X, SX, gamma,
+                       beta, mean, rstd, (int)N, (int)C, Y, SY);
+    return launch_status();
+  }
   const dim3 grid((unsigned)(N / block));
   const int nit = (int)((C + 1023) / 1024);
   const size_t lds = 16 * (size_t)(C / 32) * sizeof(float);
@@ -1507,11 +1848,23 @@ static int32_t layernorm_bwd_launch(const int8_t* dY, const float* SdY, const in
   using namespace jf;
   const int nparts = (int)ln_bwd_partial_rows(N, C, block);
   const dim3 grid((unsigned)(C > 2048 ? N / block : nparts));
-  const int nit = (int)((C + 1023) / 1024);
-  // max-abs slots per wave, (row means,) four column-sum rows
-  const size_t lds = C > 2048 ? (16 * (size_t)(C / 32) + 4 * 2 * (size_t)C) * sizeof(float)
-                              : (8 * (size_t)(C / 32) + 2 * (size_t)block + 4 * 2 * (size_t)C) * sizeof(float);
-  JF_LN_DISPATCH(launch_ln_bwd, block, nit, grid, lds, st, dY, SdY, X, SX, gamma, mean, rstd, (int)N, (int)C, dX, SdX, partials);
+  if (block == 32) {
+    // the workspace holds the partial rows, then the two row means of every row (per range of 2048 columns)
+    float* row_means = partials + (size_t)nparts * 2 * (size_t)C;
+    const int ranges = (int)((C + 2047) / 2048);
+    launch_ln_bwd_sums_strips32(C, dim3((unsigned)nparts, (unsigned)ranges), st, dY, SdY, X, SX, gamma, mean, rstd, (int)N, (int)C,
+                                row_means, partials);
+    const int32_t rc1 = launch_status();
+    if (rc1 != JF_OK) return rc1;
+    hipLaunchKernelGGL(layernorm_bwd_apply_strip32_kernel, dim3(tile_grid((C + 127) / 128, N / 32)), dim3(64), 0, st, dY, SdY, X, SX,
+                       gamma, mean, rstd, row_means, ranges, (int)N, (int)C, dX, SdX);
+  } else {
+    const int nit = (int)((C + 1023) / 1024);
+    // max-abs slots per wave, (row means,) four column-sum rows
+    const size_t lds = C > 2048 ? (16 * (size_t)(C / 32) + 4 * 2 * (size_t)C) * sizeof(float)
+                                : (8 * (size_t)(C / 32) + 2 * (size_t)block + 4 * 2 * (size_t)C) * sizeof(float);
+    JF_LN_DISPATCH(launch_ln_bwd, block, nit, grid, lds, st, dY, SdY, X, SX, gamma, mean, rstd, (int)N, (int)C, dX, SdX, partials);
+  }
   const int32_t rc = launch_status();
   if (rc != JF_OK) return rc;
   hipLaunchKernelGGL(colsum_kernel, dim3((unsigned)((2 * C + 63) / 64)), dim3(1024), 0, st, partials, nparts, (int)(2 * C), dgamma, dbeta);
@@ -1525,7 +1878,7 @@ static int32_t layernorm_bwd_check(const int8_t* dY, const float* SdY, const int
   int32_t rc = check_eltwise(X, SX, dX, SdX, N, C, block);
   if (rc != JF_OK) return rc;
   if (!dY || !SdY || !gamma || !mean || !rstd || !dgamma || !dbeta) return JF_ERR_NULL;
-  if (C > kLayerNormMaxC) return JF_ERR_SHAPE;
+  if (C > kLayerNormMaxC && block != 32) return JF_ERR_SHAPE;
   if (!aligned16(dY) || !aligned4(SdY) || !aligned16(gamma) || !aligned4(mean) || !aligned4(rstd) ||
       !aligned4(dgamma) || !aligned4(dbeta))
     return JF_ERR_ALIGN;

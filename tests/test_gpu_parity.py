@@ -364,6 +364,27 @@ def test_layernorm_fwd_bwd(block, N, C):
     assert torch.equal(dgam, dgam2) and torch.equal(dbet, dbet2) and torch.equal(dX, dX2)
 
 
+@pytest.mark.parametrize("N,C", [(64, 8192), (96, 5152), (128, 3072)])
+def test_layernorm_wide_rows(N, C):
+    """Block size 32 works on strips after a pass that only leaves sums, so rows may be wider than a workgroup could
+    hold (hidden 8192 is the widest LayerNorm the paper's speed comparison quotes); 5152 leaves a ragged last strip
+    and a last column range that uses a part of its waves."""
+    block = 32
+    say(f"layernorm wide rows {N}x{C}")
+    x, gamma, beta, gr = workloads.layernorm_case(6500 + C, N, C)
+    (X, SX), (G, SG) = oracle.quantize_block(x, block), oracle.quantize_block(gr, block)
+    Y, SY, mean, rstd = jf.jf_layernorm_q(dev(X), dev(SX), dev(gamma), dev(beta), 1e-5, block)
+    oY, oSY, omean, orstd, oy = oracle.layernorm_q(X, SX, gamma, beta, 1e-5, block)
+    np.testing.assert_allclose(host(mean), omean, rtol=0, atol=1e-5 * np.abs(oracle.dequantize(X, SX, block)).max())
+    np.testing.assert_allclose(host(rstd), orstd, rtol=1e-5)
+    _check_eltwise("layernorm fwd", Y, SY, oY, oSY, oy, block)
+    dX, SdX, dgam, dbet = jf.jf_layernorm_q_bwd(dev(G), dev(SG), dev(X), dev(SX), dev(gamma), dev(omean), dev(orstd), block)
+    odX, oSdX, odg, odb, odx = oracle.layernorm_q_bwd(G, SG, X, SX, gamma, omean, orstd, block)
+    _check_eltwise("layernorm bwd", dX, SdX, odX, oSdX, odx, block)
+    xh = (oracle.dequantize(X, SX, block) - omean[:, None].astype(np.float64)) * orstd[:, None].astype(np.float64)
+    assert_layernorm_param_grads_close(host(dgam), host(dbet), odg, odb, oracle.dequantize(G, SG, block), xh, "layernorm bwd")
+
+
 # --------------------------------------------------------------------------- Add with row partials, LayerNorm from them
 @pytest.mark.parametrize("block,N,C", [(32, 96, 352), (64, 128, 192), (128, 256, 384), (32, 8192, 1280)])
 def test_add_and_layernorm_from_partials(block, N, C):

@@ -137,6 +137,18 @@ int32_t jf_linear_wgrad(const int8_t* dY, const float* SdY, const int8_t* X, con
                         void* stream);
 
 /*
+ * Both backward products of a layer in one call (Sec. 4): dX = dY W exactly
+ * as jf_linear_dgrad and dW = dY^T X exactly as jf_linear_wgrad, same
+ * arguments, same results bit for bit.  The two products need the same dY
+ * and nothing of each other; for layers whose products are too small to fill
+ * the chip one by one (block 32, outputs of a few hundred 64 x 64 tiles) they
+ * run as ONE kernel launch, otherwise as two.
+ */
+int32_t jf_linear_bwd(const int8_t* dY, const float* SdY, const int8_t* W, const float* SW, const int8_t* X,
+                      const float* SX, int64_t N, int64_t C, int64_t D, int32_t block, int8_t* dX, float* SdX,
+                      float* dX_f32, int8_t* dW, float* SdW, float* dW_f32, void* ws, size_t ws_bytes, void* stream);
+
+/*
  * INT8 GELU (Sec. 6, Alg. 2; App. A: GELU(x) = x Phi(x), exact-erf form).
  * X N x C codes + SX  ->  Y N x C codes + SY.
  */

@@ -18,6 +18,7 @@ from .binding import (  # noqa: F401
     jf_layernorm_q_bwd,
     jf_layernorm_q_bwd_static,
     jf_layernorm_q_partials,
+    jf_linear_bwd,
     jf_linear_dgrad,
     jf_linear_fwd,
     jf_linear_wgrad,

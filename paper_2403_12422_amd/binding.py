@@ -22,6 +22,7 @@ _SIGNATURES = {
     "jf_linear_fwd": (_I32, [_P, _P, _P, _P, _I64, _I64, _I64, _I32, _P, _P, _P, _P, _SZ, _P]),
     "jf_linear_dgrad": (_I32, [_P, _P, _P, _P, _I64, _I64, _I64, _I32, _P, _P, _P, _P, _SZ, _P]),
     "jf_linear_wgrad": (_I32, [_P, _P, _P, _P, _I64, _I64, _I64, _I32, _P, _P, _P, _P, _SZ, _P]),
+    "jf_linear_bwd": (_I32, [_P, _P, _P, _P, _P, _P, _I64, _I64, _I64, _I32, _P, _P, _P, _P, _P, _P, _P, _SZ, _P]),
     "jf_gelu_q": (_I32, [_P, _P, _I64, _I64, _I32, _P, _P, _P]),
     "jf_gelu_q_bwd": (_I32, [_P, _P, _P, _P, _I64, _I64, _I32, _P, _P, _P]),
     "jf_layernorm_q": (_I32, [_P, _P, _P, _P, _F32, _I64, _I64, _I32, _P, _P, _P, _P, _P]),
@@ -173,6 +174,30 @@ def jf_linear_wgrad(dY, SdY, X, SX, block=32, want_q=True, want_f32=False, out=N
     if X.shape[0] != N:
         raise JetfireError(2, "dY and X disagree on N")
     return _linear(load_library().jf_linear_wgrad, dY, SdY, X, SX, N, C, D, block, (D, C), want_q, want_f32, out)
+
+
+def jf_linear_bwd(dY, SdY, W, SW, X, SX, block=32, want_f32=False, out=None):
+    """Both backward products in one call: returns ((dX, SdX, dX_f32 or None), (dW, SdW, dW_f32 or None)); `out` is the
+    same pair of triples, preallocated."""
+    for t in (dY, W, X):
+        _dev(t, torch.int8, 2)
+    for t in (SdY, SW, SX):
+        _dev(t, torch.float32, 2)
+    N, D = dY.shape
+    C = W.shape[1]
+    if W.shape[0] != D or tuple(X.shape) != (N, C):
+        raise JetfireError(2, "dY, W and X disagree on N, C, D")
+    dev = dY.device
+    if out is not None:
+        (dX, SdX, dXf), (dW, SdW, dWf) = out
+    else:
+        i8 = lambda r, c: torch.empty((r, c), dtype=torch.int8, device=dev)
+        sc = lambda r, c: torch.empty((r // block, c // block), dtype=torch.float32, device=dev)
+        f32 = lambda r, c: torch.empty((r, c), dtype=torch.float32, device=dev) if want_f32 else None
+        dX, SdX, dXf, dW, SdW, dWf = i8(N, C), sc(N, C), f32(N, C), i8(D, C), sc(D, C), f32(D, C)
+    _check(load_library().jf_linear_bwd(_ptr(dY), _ptr(SdY), _ptr(W), _ptr(SW), _ptr(X), _ptr(SX), N, C, D, block, _ptr(dX),
+                                        _ptr(SdX), _ptr(dXf), _ptr(dW), _ptr(SdW), _ptr(dWf), None, 0, _stream()))
+    return (dX, SdX, dXf), (dW, SdW, dWf)
 
 
 def jf_gelu_q(X, SX, block=32, out=None):

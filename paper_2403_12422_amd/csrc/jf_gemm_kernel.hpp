@@ -185,42 +185,57 @@ __device__ __forceinline__ void fold(float (&acc)[16], const v16i& v, float t) {
   }
 }
 
-// WMIN = minimum resident waves per SIMD the register allocation must allow.
+// Compile-time shape of one kernel instance: tile, stage and LDS ring.
 // DEEP: a stage of 128 K bytes where the shape's default is 64.
-template <int B, int WM, int WN, int WGM, int WGN, bool AK, bool BK, bool DUMP, int WMIN, bool DEEP = false>
-__global__ void __launch_bounds__(64 * WGM * WGN, WMIN) gemm_kernel(const GemmArgs g) {
-  constexpr int NW = WGM * WGN;
-  constexpr int TM = 32 * WM * WGM, TN = 32 * WN * WGN;
-  constexpr int KPB = B / 32;  // MFMA K steps per quantization block
+template <int B, int WM, int WN, int WGM, int WGN, bool AK, bool BK, bool DEEP>
+struct GemmShape {
+  static constexpr int NW = WGM * WGN;
+  static constexpr int TM = 32 * WM * WGM, TN = 32 * WN * WGN;
   // K bytes per stage: 128 when a stage has to hold a whole B = 128 block, for the workgroups of more than
   // four waves of fewer than four sub-blocks each (one workgroup per compute unit, whose barriers are the most
   // expensive), and for the one-sub-block waves at B = 64 (a stage must hold an even number of sub-block x
   // K-block units); 64 otherwise, which lets three workgroups with a ring of three stages share the LDS of a
   // compute unit.
-  constexpr int KC = (DEEP || B == 128 || (WGM * WGN > 4 && WM * WN < 4) || (B == 64 && WM * WN == 1)) ? 128 : 64;
-  constexpr int SPS = KC / 32;  // MFMA K steps per stage
-  constexpr int NTILE = WM * WN;
+  static constexpr int KC = (DEEP || B == 128 || (WGM * WGN > 4 && WM * WN < 4) || (B == 64 && WM * WN == 1)) ? 128 : 64;
   typedef TileLayout<TM, AK, KC> LA;
   typedef TileLayout<TN, BK, KC> LB;
-  constexpr int A_BYTES = LA::bytes(NW), B_BYTES = LB::bytes(NW);
-  constexpr int CA = A_BYTES / (1024 * NW), CB = B_BYTES / (1024 * NW);  // load instructions per wave and stage
-  static_assert(B == 32 || (TM % B == 0 && TN % B == 0), "tile must hold whole quantization blocks");
-  constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
-
+  static constexpr int A_BYTES = LA::bytes(NW), B_BYTES = LB::bytes(NW);
+  static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
   // Stages in the LDS ring: one being read, the rest in flight.  Tiles that leave a compute unit to a single
   // workgroup (more than four waves) take a ring of four if that fits the LDS, the others a ring of three.
-  constexpr int NBUF = (NW > 4 && 4 * STAGE_BYTES <= 156 * 1024) ? 4 : 3;
+  static constexpr int NBUF = (NW > 4 && 4 * STAGE_BYTES <= 156 * 1024) ? 4 : 3;
   static_assert(NBUF * STAGE_BYTES <= 160 * 1024, "the ring must fit the LDS of a compute unit");
-  // One LDS variable per ring slot: the compiler tracks direct-to-LDS loads per variable, so a read of
-  // one slot does not make it wait for the loads still flying into the other slots.
-  __shared__ __align__(1024) int8_t s_tile0[STAGE_BYTES];
-  __shared__ __align__(1024) int8_t s_tile1[STAGE_BYTES];
-  __shared__ __align__(1024) int8_t s_tile2[NBUF > 2 ? STAGE_BYTES : 16];
-  __shared__ __align__(1024) int8_t s_tile3[NBUF > 3 ? STAGE_BYTES : 16];
+  static constexpr int RING_BYTES = NBUF * STAGE_BYTES;
+};
+
+// One output tile: K loop and epilogue.  `tile_index` of `ntiles` is this workgroup's position in the launch (or in
+// its part of a launch that holds two products); s_ring is the workgroup's LDS ring of NBUF stages, s_amax its
+// max-abs exchange area, both owned by the calling kernel.
+template <int B, int WM, int WN, int WGM, int WGN, bool AK, bool BK, bool DUMP, bool DEEP>
+__device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int tile_index, const int ntiles, int8_t* const s_ring,
+                                          float (*const s_amax)[8]) {
+  typedef GemmShape<B, WM, WN, WGM, WGN, AK, BK, DEEP> Shape;
+  constexpr int NW = Shape::NW;
+  constexpr int TM = Shape::TM, TN = Shape::TN;
+  constexpr int KPB = B / 32;  // MFMA K steps per quantization block
+  constexpr int KC = Shape::KC;
+  constexpr int SPS = KC / 32;  // MFMA K steps per stage
+  constexpr int NTILE = WM * WN;
+  typedef typename Shape::LA LA;
+  typedef typename Shape::LB LB;
+  constexpr int A_BYTES = Shape::A_BYTES, B_BYTES = Shape::B_BYTES;
+  constexpr int CA = A_BYTES / (1024 * NW), CB = B_BYTES / (1024 * NW);  // load instructions per wave and stage
+  static_assert(B == 32 || (TM % B == 0 && TN % B == 0), "tile must hold whole quantization blocks");
+  constexpr int STAGE_BYTES = Shape::STAGE_BYTES;
+  constexpr int NBUF = Shape::NBUF;
+  static_assert(TM / 32 <= 8 && TN / 32 <= 8, "max-abs exchange area");
+  int8_t* const s_tile0 = s_ring;
+  int8_t* const s_tile1 = s_ring + STAGE_BYTES;
+  int8_t* const s_tile2 = s_ring + 2 * STAGE_BYTES;
+  int8_t* const s_tile3 = s_ring + (NBUF > 3 ? 3 : 2) * STAGE_BYTES;
   auto tile_buf = [&](int buf) -> int8_t* {
     return buf == 0 ? s_tile0 : (buf == 1 ? s_tile1 : (buf == 2 ? s_tile2 : s_tile3));
   };
-  __shared__ float s_amax[TM / 32][TN / 32];
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -231,8 +246,8 @@ __global__ void __launch_bounds__(64 * WGM * WGN, WMIN) gemm_kernel(const GemmAr
   // inside a group: the workgroups that are resident on an XCD at the same time then form a compact patch
   // (8 tile rows x a few tile columns) that re-reads few distinct operand tiles from that XCD's L2.
   constexpr int GROUP_M = TM >= 256 ? 4 : 8;
-  const int ntiles = gridDim.x, tiles_n = (g.Nn + TN - 1) / TN, tiles_m = (g.M + TM - 1) / TM;
-  const int xcd = blockIdx.x & 7, idx = blockIdx.x >> 3;
+  const int tiles_n = (g.Nn + TN - 1) / TN, tiles_m = (g.M + TM - 1) / TM;
+  const int xcd = tile_index & 7, idx = tile_index >> 3;
   const int tile = xcd * (ntiles >> 3) + min(xcd, ntiles & 7) + idx;
   const int group = tile / (GROUP_M * tiles_n), first_m = group * GROUP_M;
   const int in_group = tile - group * GROUP_M * tiles_n, group_rows = min(GROUP_M, tiles_m - first_m);
@@ -629,6 +644,40 @@ __global__ void __launch_bounds__(64 * WGM * WGN, WMIN) gemm_kernel(const GemmAr
   }
 }
 
+// One product per launch.  WMIN = minimum resident waves per SIMD the register allocation must allow.
+template <int B, int WM, int WN, int WGM, int WGN, bool AK, bool BK, bool DUMP, int WMIN, bool DEEP = false>
+__global__ void __launch_bounds__(64 * WGM * WGN, WMIN) gemm_kernel(const GemmArgs g) {
+  typedef GemmShape<B, WM, WN, WGM, WGN, AK, BK, DEEP> Shape;
+  __shared__ __align__(1024) int8_t s_ring[Shape::RING_BYTES];
+  __shared__ float s_amax[8][8];
+  gemm_tile<B, WM, WN, WGM, WGN, AK, BK, DUMP, DEEP>(g, blockIdx.x, gridDim.x, s_ring, s_amax);
+}
+
+// Two independent products in one launch -- the input gradient and the weight gradient of a layer (Sec. 4), which
+// need the same dY and nothing of each other.  Workgroups 0 .. tiles_first - 1 take tiles of the first product, the
+// others of the second; both use four-wave workgroups, so the ring is the larger of the two.  Each product alone
+// has too few tiles to keep the chip busy to the end, and pays its own ramp-up, first-stage latency and epilogue;
+// in one launch the scheduler starts tiles of the second as those of the first finish, so that those phases of
+// some workgroups run beside the K loops of others.
+template <class First, class Second, int WMIN>
+__global__ void __launch_bounds__(256, WMIN) gemm_pair_kernel(const GemmArgs g1, const GemmArgs g2, const int tiles_first) {
+  constexpr int RING = First::Shape::RING_BYTES > Second::Shape::RING_BYTES ? First::Shape::RING_BYTES : Second::Shape::RING_BYTES;
+  __shared__ __align__(1024) int8_t s_ring[RING];
+  __shared__ float s_amax[8][8];
+  if ((int)blockIdx.x < tiles_first) First::run(g1, blockIdx.x, tiles_first, s_ring, s_amax);
+  else Second::run(g2, blockIdx.x - tiles_first, gridDim.x - tiles_first, s_ring, s_amax);
+}
+// a product's instance as a type, for gemm_pair_kernel
+template <int B, int WM, int WN, int WGM, int WGN, bool AK, bool BK, bool DEEP>
+struct GemmInstance {
+  typedef GemmShape<B, WM, WN, WGM, WGN, AK, BK, DEEP> Shape;
+  static_assert(Shape::NW == 4, "pairs are built from four-wave workgroups");
+  static __device__ __forceinline__ void run(const GemmArgs& g, int tile_index, int ntiles, int8_t* s_ring, float (*s_amax)[8]) {
+    gemm_tile<B, WM, WN, WGM, WGN, AK, BK, false, DEEP>(g, tile_index, ntiles, s_ring, s_amax);
+  }
+  static int tiles(const GemmArgs& a) { return ((a.M + Shape::TM - 1) / Shape::TM) * ((a.Nn + Shape::TN - 1) / Shape::TN); }
+};
+
 // --------------------------------------------------------------------- host
 template <int B, int WM, int WN, int WGM, int WGN, bool AK, bool BK, bool DUMP, bool DEEP = false>
 static void launch_cfg(const GemmArgs& a, hipStream_t st) {
@@ -665,6 +714,29 @@ static ShapeCost shape_cost(const GemmArgs& a, int tm, int tn, int waves, int ti
   const int64_t stage = q * (int64_t)(tm + tn) * a.K / 28;           // ~28 bytes per cycle of L2 -> LDS per compute unit
   return {valu > stage ? valu : stage};
 }
+// Tile shape of a block-32 product, numbered as in jf_debug_set_gemm_shape: 1 128x128, 2 128x96, 3 96x96, 4 64x64,
+// 7 64x64 with a stage of 128 K bytes.
+template <bool AK, bool BK>
+static int choose_shape_b32(const GemmArgs& a) {
+  int64_t c128 = shape_cost(a, 128, 128, 4, 4).cycles;
+  int64_t c12896 = shape_cost(a, 128, 96, 12, 1).cycles;
+  int64_t c9696 = shape_cost(a, 96, 96, 9, 1).cycles;
+  int64_t c64 = shape_cost(a, 64, 64, 4, 1).cycles;
+  if (g_forced_shape) {
+    const int64_t big = INT64_MAX;
+    c128 = g_forced_shape == 1 ? 0 : big;
+    c12896 = g_forced_shape == 2 ? 0 : big;
+    c9696 = g_forced_shape == 3 ? 0 : big;
+    c64 = (g_forced_shape == 4 || g_forced_shape == 7) ? 0 : big;
+  }
+  if (c128 <= c12896 && c128 <= c9696 && c128 <= c64) return 1;
+  if (c12896 <= c9696 && c12896 <= c64) return 2;
+  if (c9696 <= c64) return 3;
+  const int64_t n64 = (int64_t)((a.M + 63) / 64) * ((a.Nn + 63) / 64);
+  const bool deep = g_forced_shape ? g_forced_shape == 7 : ((AK || BK) && n64 <= 768);
+  return deep ? 7 : 4;
+}
+
 template <int B, bool AK, bool BK, bool DUMP>
 static void launch_shape(const GemmArgs& a, hipStream_t st) {
   if (g_forced_shape == 6) {
@@ -686,26 +758,12 @@ static void launch_shape(const GemmArgs& a, hipStream_t st) {
     else
       launch_cfg<B, 1, 1, 2, 2, AK, BK, DUMP>(a, st);
   } else {
-    int64_t c128 = shape_cost(a, 128, 128, 4, 4).cycles;
-    int64_t c12896 = shape_cost(a, 128, 96, 12, 1).cycles;
-    int64_t c9696 = shape_cost(a, 96, 96, 9, 1).cycles;
-    int64_t c64 = shape_cost(a, 64, 64, 4, 1).cycles;
-    if (g_forced_shape) {
-      const int64_t big = INT64_MAX;
-      c128 = g_forced_shape == 1 ? 0 : big;
-      c12896 = g_forced_shape == 2 ? 0 : big;
-      c9696 = g_forced_shape == 3 ? 0 : big;
-      c64 = (g_forced_shape == 4 || g_forced_shape == 7) ? 0 : big;
-    }
-    if (c128 <= c12896 && c128 <= c9696 && c128 <= c64) launch_cfg<B, 2, 2, 2, 2, AK, BK, DUMP>(a, st);
-    else if (c12896 <= c9696 && c12896 <= c64) launch_cfg<B, 1, 1, 4, 3, AK, BK, DUMP>(a, st);
-    else if (c9696 <= c64) launch_cfg<B, 1, 1, 3, 3, AK, BK, DUMP>(a, st);
-    else {
-      const int64_t n64 = (int64_t)((a.M + 63) / 64) * ((a.Nn + 63) / 64);
-      const bool deep = g_forced_shape ? g_forced_shape == 7 : ((AK || BK) && n64 <= 768);
-      if (deep) launch_cfg<B, 1, 1, 2, 2, AK, BK, DUMP, true>(a, st);
-      else launch_cfg<B, 1, 1, 2, 2, AK, BK, DUMP>(a, st);
-    }
+    const int shape = choose_shape_b32<AK, BK>(a);
+    if (shape == 1) launch_cfg<B, 2, 2, 2, 2, AK, BK, DUMP>(a, st);
+    else if (shape == 2) launch_cfg<B, 1, 1, 4, 3, AK, BK, DUMP>(a, st);
+    else if (shape == 3) launch_cfg<B, 1, 1, 3, 3, AK, BK, DUMP>(a, st);
+    else if (shape == 7) launch_cfg<B, 1, 1, 2, 2, AK, BK, DUMP, true>(a, st);
+    else launch_cfg<B, 1, 1, 2, 2, AK, BK, DUMP>(a, st);
   }
 }
 
@@ -719,5 +777,24 @@ static void launch_product(const GemmArgs& a, bool dump, hipStream_t st) {
 
 #define JF_GEMM_INSTANCE(NAME, B, AK, BK) \
   namespace jf { void NAME(const GemmArgs& a, bool dump, hipStream_t st) { launch_product<B, AK, BK>(a, dump, st); } }
+
+#ifdef JF_GEMM_PAIR_INSTANCES   // defined by the one translation unit that holds the pair kernels
+// Input gradient and weight gradient of a block-32 layer in one launch (gemm_pair_kernel), when each of them alone
+// would run on 64 x 64 tiles, i.e. has too few tiles for the larger shapes.  The weight gradient's tiles, whose K loop
+// over the tokens is the longer one, are dealt first.  Returns false (nothing launched) when the shapes do not suit.
+static bool launch_bwd_pair_b32(const GemmArgs& dgrad, const GemmArgs& wgrad, hipStream_t st) {
+  typedef GemmInstance<32, 1, 1, 2, 2, false, false, false> Wgrad;
+  typedef GemmInstance<32, 1, 1, 2, 2, true, false, false> Dgrad;
+  typedef GemmInstance<32, 1, 1, 2, 2, true, false, true> DgradDeep;
+  const int sd = choose_shape_b32<true, false>(dgrad), sw = choose_shape_b32<false, false>(wgrad);
+  if ((sd != 4 && sd != 7) || sw != 4) return false;
+  // the first part is padded to a multiple of 8 workgroups so that both parts see the same XCD numbering
+  const int tw = Wgrad::tiles(wgrad), td = Dgrad::tiles(dgrad);
+  if (tw % 8) return false;
+  if (sd == 7) hipLaunchKernelGGL((gemm_pair_kernel<Wgrad, DgradDeep, 3>), dim3(tw + td), dim3(256), 0, st, wgrad, dgrad, tw);
+  else hipLaunchKernelGGL((gemm_pair_kernel<Wgrad, Dgrad, 3>), dim3(tw + td), dim3(256), 0, st, wgrad, dgrad, tw);
+  return true;
+}
+#endif
 
 }  // namespace jf

@@ -14,6 +14,7 @@ void launch_gemm_dgrad_b128(const GemmArgs& a, bool dump, hipStream_t st);
 void launch_gemm_wgrad_b32(const GemmArgs& a, bool dump, hipStream_t st);
 void launch_gemm_wgrad_b64(const GemmArgs& a, bool dump, hipStream_t st);
 void launch_gemm_wgrad_b128(const GemmArgs& a, bool dump, hipStream_t st);
+bool launch_gemm_bwd_pair_b32(const GemmArgs& dgrad, const GemmArgs& wgrad, hipStream_t st);
 
 int g_forced_shape = 0;
 
@@ -107,6 +108,31 @@ extern "C" int32_t jf_linear_wgrad(const int8_t* dY, const float* SdY, const int
   GemmArgs g = make_args(2, dY, SdY, X, SX, N, C, D, block);
   g.Oq = dW; g.Os = SdW; g.Of = dW_f32;
   launch_gemm(2, block, g, false, reinterpret_cast<hipStream_t>(stream));
+  return launch_status();
+}
+
+extern "C" int32_t jf_linear_bwd(const int8_t* dY, const float* SdY, const int8_t* W, const float* SW, const int8_t* X,
+                                 const float* SX, int64_t N, int64_t C, int64_t D, int32_t block, int8_t* dX, float* SdX,
+                                 float* dX_f32, int8_t* dW, float* SdW, float* dW_f32, void* ws, size_t ws_bytes,
+                                 void* stream) {
+  using namespace jf;
+  (void)ws; (void)ws_bytes;
+  int32_t rc = check_linear(dY, SdY, W, SW, N, C, D, block);
+  if (rc == JF_OK) rc = check_linear(dY, SdY, X, SX, N, C, D, block);
+  if (rc == JF_OK) rc = check_out(dX, SdX, dX_f32, true);
+  if (rc == JF_OK) rc = check_out(dW, SdW, dW_f32, false);
+  if (rc != JF_OK) return rc;
+  GemmArgs gd = make_args(1, dY, SdY, W, SW, N, C, D, block);
+  gd.Oq = dX; gd.Os = SdX; gd.Of = dX_f32;
+  GemmArgs gw = make_args(2, dY, SdY, X, SX, N, C, D, block);
+  gw.Oq = dW; gw.Os = SdW; gw.Of = dW_f32;
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  if (block != 32 || !launch_gemm_bwd_pair_b32(gd, gw, st)) {   // shapes that fill the chip on their own: two launches
+    launch_gemm(1, block, gd, false, st);
+    rc = launch_status();
+    if (rc != JF_OK) return rc;
+    launch_gemm(2, block, gw, false, st);
+  }
   return launch_status();
 }
 

@@ -468,3 +468,26 @@ def test_linear_config5_sweep_sampled(N, C, D, block):
     _check_sampled("wgrad", jf.jf_linear_wgrad(dYd, SdYd, Xd, SXd, block, want_f32=True), dYT, SdYT, XT, SXT, block, g, nblk,
                    without_f32=jf.jf_linear_wgrad(dYd, SdYd, Xd, SXd, block))
     torch.cuda.empty_cache()
+
+
+# --------------------------------------------------------------------------- both backward products in one call
+@pytest.mark.parametrize("block,N,C,D", [(32, 4096, 768, 3072), (32, 416, 96, 224), (32, 512, 640, 256), (32, 2048, 2048, 2048),
+                                         (64, 256, 192, 320), (128, 384, 256, 640)])
+def test_linear_bwd_equals_dgrad_and_wgrad(block, N, C, D):
+    """jf_linear_bwd (one launch for both products where each alone is too small to fill the chip, else two) gives
+    what jf_linear_dgrad and jf_linear_wgrad give, bit for bit; those are checked against the oracle above."""
+    say(f"linear bwd block={block} N={N} C={C} D={D}")
+    (X, SX), (W, SW), (dY, SdY) = _quantized_layer(4700 + N + block, N, C, D, block)
+    Xd, SXd, Wd, SWd, dYd, SdYd = map(dev, (X, SX, W, SW, dY, SdY))
+    for want_f32 in (True, False):
+        wd = jf.jf_linear_dgrad(dYd, SdYd, Wd, SWd, block, want_f32=want_f32)
+        ww = jf.jf_linear_wgrad(dYd, SdYd, Xd, SXd, block, want_f32=want_f32)
+        gd, gw = jf.jf_linear_bwd(dYd, SdYd, Wd, SWd, Xd, SXd, block, want_f32=want_f32)
+        for got, want in ((gd, wd), (gw, ww)):
+            for g_, w_ in zip(got, want):
+                assert (g_ is None and w_ is None) or torch.equal(g_, w_)
+    if (block, N, C, D) == (32, 416, 96, 224):                 # ragged tiles in both products: also against the oracle
+        _check_linear("bwd: dgrad", jf.jf_linear_bwd(dYd, SdYd, Wd, SWd, Xd, SXd, block, want_f32=True)[0],
+                      oracle.linear_dgrad(dY, SdY, W, SW, block), block)
+        _check_linear("bwd: wgrad", jf.jf_linear_bwd(dYd, SdYd, Wd, SWd, Xd, SXd, block, want_f32=True)[1],
+                      oracle.linear_wgrad(dY, SdY, X, SX, block), block)

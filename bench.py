@@ -5,11 +5,13 @@ One "step" is one pass of the whole hot path over one synthetic batch at the GPT
 (tokens 4096, in 768, out 3072, block 32), every tensor already resident in HBM:
 
     quantize X, W, dH  ->  LayerNorm fwd  ->  linear fwd  ->  GELU fwd  ->  GELU bwd
-                       ->  linear dgrad   ->  linear wgrad ->  LayerNorm bwd
+                       ->  linear dgrad + wgrad (one call, jf_linear_bwd)  ->  LayerNorm bwd
 
 `value` is 6*N*C*D INT8 ops (forward + dgrad + wgrad) divided by the wall time of the WHOLE step, i.e. it
 charges the quantize / GELU / LayerNorm time to the linear layer as well.  The roofline object describes the
-GEMM kernel (three launches per step), timed with HIP events around each launch inside the timed region.
+GEMM kernels (two launches per step: the forward product, and both backward products in one grid), timed in
+loops of their own -- 5 x 100 back-to-back launches each between HIP events on the launch stream -- and, as a
+cross-check, by events around their launches on every n-th step of the timed region.
 """
 import argparse
 import json
@@ -39,7 +41,9 @@ def parse_args():
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="oracle time budget of the CPU baseline leg")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also launch plain 256 MiB device copies, the reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE")
-    ap.add_argument("--event-every", type=int, default=8,
+    ap.add_argument("--no-extra-configs", action="store_true",
+                    help="skip the compact config 4 (transformer block) and config 5 (large GEMMs) records of the default line")
+    ap.add_argument("--event-every", type=int, default=4,
                     help="bracket the GEMM launches with HIP events on every n-th timed step only")
     ap.add_argument("--no-hbm-sized-ops", action="store_true",
                     help="skip timing GELU / LayerNorm / quantize on tensors too large for the last-level cache")
@@ -58,19 +62,19 @@ def parse_args():
 
 
 def cpu_baseline(args, N, C, D, block):
-    """Time the unmodified oracle on the host cores on a token slice of the same workload."""
+    """Time the unmodified oracle on the host cores: the whole step on all cores, the same step on a token slice
+    on one core, and (config 5) a sample of output blocks of the 8192^3 forward product, extrapolated."""
     import numpy as np
     import oracle
     from paper_2403_12422_amd import workloads
 
-    n = min(args.cpu_sample_tokens, N)
-    X, W, dH = workloads.linear_layer(2, n, C, D)
     g = workloads.rng(77)
     gamma = (1.0 + 0.1 * g.standard_normal(C, dtype=np.float32)).astype(np.float32)
     beta = (0.1 * g.standard_normal(C, dtype=np.float32)).astype(np.float32)
-    oracle.quantize_block(X[:block], block)            # load the library outside the timed part
+    Xf, W, dHf = workloads.linear_layer(2, N, C, D)
+    oracle.quantize_block(Xf[:block], block)            # load the library outside the timed part
 
-    def oracle_step():
+    def oracle_step(X, dH):
         Xq, SX = oracle.quantize_block(X, block)
         Wq, SW = oracle.quantize_block(W, block)
         Gq, SG = oracle.quantize_block(dH, block)
@@ -82,23 +86,50 @@ def cpu_baseline(args, N, C, D, block):
         oracle.linear_wgrad(dY, SdY, Xn, SXn, block)
         oracle.layernorm_q_bwd(dXn, SdXn, Xq, SX, gamma, mean, rstd, block)
 
-    reps = 0
-    t0 = time.perf_counter()
-    while True:                                        # repeat the step until about 10 s of oracle time
-        oracle_step()
-        reps += 1
-        dt = time.perf_counter() - t0
-        if dt >= args.cpu_seconds or reps >= 64:
-            break
-    dt /= reps
-    return {
-        "value": 6.0 * n * C * D / dt * 1e-12,
+    def timed(fn, seconds, max_reps):
+        reps, t0 = 0, time.perf_counter()
+        while True:
+            fn()
+            reps += 1
+            dt = time.perf_counter() - t0
+            if dt >= seconds or reps >= max_reps:
+                return dt / reps, reps
+
+    cores = oracle.max_threads()
+    n = min(args.cpu_sample_tokens, N)
+    dt_all, reps_all = timed(lambda: oracle_step(Xf[:n], dHf[:n]), args.cpu_seconds, 64)
+    # one core: a slice of 512 tokens (weights full size), so that the leg stays within seconds
+    n1 = min(512, n)
+    oracle.set_threads(1)
+    dt_one, reps_one = timed(lambda: oracle_step(Xf[:n1], dHf[:n1]), 0.4 * args.cpu_seconds, 8)
+    oracle.set_threads(cores)
+    out = {
+        "value": 6.0 * n * C * D / dt_all * 1e-12,
         "unit": "TOPS",
-        "cores": oracle.max_threads(),
+        "cores": cores,
         "kind": "oracle",
-        "sample": f"whole step on the first {n} of {N} tokens (weights full size), {reps} repetitions, "
-                  f"{dt:.2f} s of oracle time each",
+        "sample": f"whole step on the first {n} of {N} tokens (weights full size), {reps_all} repetitions, "
+                  f"{dt_all:.2f} s of oracle time each",
+        "single_thread": {"value": 6.0 * n1 * C * D / dt_one * 1e-12, "unit": "TOPS", "cores": 1,
+                          "sample": f"whole step on the first {n1} tokens, {reps_one} repetitions, {dt_one:.2f} s each"},
     }
+    if not args.no_extra_configs:
+        # config 5: 8192^3 forward product at block 32, a seeded sample of 256 output blocks (each over the full K;
+        # blocks are independent), extrapolated to the 65536 blocks of the product
+        M = 8192
+        gq = workloads.rng(85)
+        A = gq.integers(-127, 128, size=(M, M), dtype=np.int8)
+        Bm = gq.integers(-127, 128, size=(M, M), dtype=np.int8)
+        SA = gq.random((M // 32, M // 32), dtype=np.float32) + np.float32(0.01)
+        SB = gq.random((M // 32, M // 32), dtype=np.float32) + np.float32(0.01)
+        flat = gq.choice((M // 32) ** 2, size=256, replace=False)
+        t0 = time.perf_counter()
+        oracle.linear_nt_blocks(A, SA, Bm, SB, flat // (M // 32), flat % (M // 32), 32)
+        dt = time.perf_counter() - t0
+        out["config5_8192_cubed_block32_fwd"] = {
+            "value": 2.0 * 256 * 32 * 32 * M / dt * 1e-12, "unit": "TOPS", "cores": cores,
+            "sample": f"256 of 65536 output blocks in {dt:.2f} s; the whole product extrapolates to {dt * 256:.0f} s"}
+    return out
 
 
 SWEEP_SHAPES = [  # (tokens N, in C, out D)
@@ -107,7 +138,7 @@ SWEEP_SHAPES = [  # (tokens N, in C, out D)
 ]
 
 
-def sweep(args):
+def sweep(args, shapes=None, emit=True):
     """Large-GEMM sweep (config 5): kernel time of each product from HIP events around back-to-back launches.
 
     Values are N(0,1) with 0.5 % outlier columns x50, drawn on the GPU (torch.randn, seeded) because the largest
@@ -149,7 +180,8 @@ def sweep(args):
     jf.jf_debug_set_gemm_shape(args.sweep_shape)
     records = []
     blocks = [int(b) for b in args.sweep_blocks.split(",")]
-    shapes = [tuple(int(v) for v in args.sweep_only.split(","))] if args.sweep_only else SWEEP_SHAPES
+    if shapes is None:
+        shapes = [tuple(int(v) for v in args.sweep_only.split(","))] if args.sweep_only else SWEEP_SHAPES
     for (N, C, D) in shapes:
         if max(N, C, D) > args.sweep_max_dim:
             continue
@@ -174,12 +206,16 @@ def sweep(args):
                    "TOPS": {k: round(v, 1) for k, v in tops.items()},
                    "TOPS_fwd_dgrad_wgrad": round(total, 1), "frac_int8_mfma_peak": round(total / INT8_MFMA_PEAK_TOPS, 4)}
             records.append(rec)
-            print(f"# sweep {N}x{C}->{D} block {B}: " + ", ".join(f"{k} {ms[k]:.3f} ms {tops[k]:.0f} TOP/s" for k in ms)
-                  + f" | all three {total:.0f} TOP/s ({100 * total / INT8_MFMA_PEAK_TOPS:.1f} % of INT8 MFMA peak)",
-                  file=sys.stderr, flush=True)
+            if emit:
+                print(f"# sweep {N}x{C}->{D} block {B}: " + ", ".join(f"{k} {ms[k]:.3f} ms {tops[k]:.0f} TOP/s" for k in ms)
+                      + f" | all three {total:.0f} TOP/s ({100 * total / INT8_MFMA_PEAK_TOPS:.1f} % of INT8 MFMA peak)",
+                      file=sys.stderr, flush=True)
             del Xq, Wq, Gq, oY, odX, odW
         del Xf, Wf, Gf
         torch.cuda.empty_cache()
+    jf.jf_debug_set_gemm_shape(0)
+    if not emit:
+        return records
     best = max(records, key=lambda r: r["TOPS_fwd_dgrad_wgrad"])
     print(json.dumps({
         "metric": "per-block INT8 linear TOPS (fwd+dgrad+wgrad), large-GEMM sweep", "unit": "TOPS",
@@ -188,7 +224,7 @@ def sweep(args):
         "peak_TOPS": INT8_MFMA_PEAK_TOPS, "sweep": records}), flush=True)
 
 
-def block_layer(args):
+def block_layer(args, emit=True):
     """Config 4: one GPT-2-large-shaped transformer block (hidden 1280, 20 heads, FFN 5120, 8 x 1024 tokens, block 32),
     forward + backward with the INT8 data flow between the layers; no bias, no dropout.  The attention core is the
     stock torch FP16 scaled_dot_product_attention (forward and autograd backward); it is timed on its own as well and
@@ -241,20 +277,16 @@ def block_layer(args):
         H2, SH2, _ = jf.jf_linear_fwd(GE, SGE, W2, SW2, B)
         jf.jf_add_q(R1, SR1, H2, SH2, B)
         # backward
-        dGE, SdGE, _ = jf.jf_linear_dgrad(dY, SdY, W2, SW2, B)
-        jf.jf_linear_wgrad(dY, SdY, GE, SGE, B)
+        (dGE, SdGE, _), _ = jf.jf_linear_bwd(dY, SdY, W2, SW2, GE, SGE, B)
         dH1, SdH1 = jf.jf_gelu_q_bwd(dGE, SdGE, H1, SH1, B)
-        dA2, SdA2, _ = jf.jf_linear_dgrad(dH1, SdH1, W1, SW1, B)
-        jf.jf_linear_wgrad(dH1, SdH1, A2, SA2, B)
+        (dA2, SdA2, _), _ = jf.jf_linear_bwd(dH1, SdH1, W1, SW1, A2, SA2, B)
         dR1a, SdR1a, _, _ = jf.jf_layernorm_q_bwd(dA2, SdA2, R1, SR1, g2, mean2, rstd2, B, workspace=ws)
         dR1, SdR1 = jf.jf_add_q(dY, SdY, dR1a, SdR1a, B)
-        dAT, SdAT, _ = jf.jf_linear_dgrad(dR1, SdR1, Wo, SWo, B)
-        jf.jf_linear_wgrad(dR1, SdR1, AT, SAT, B)
+        (dAT, SdAT, _), _ = jf.jf_linear_bwd(dR1, SdR1, Wo, SWo, AT, SAT, B)
         dat16 = jf.jf_dequantize_block(dAT, SdAT, B, torch.float16)
         _, dqkv16 = attention(qkv16, dat16)
         dQKV, SdQKV = jf.jf_quantize_block(dqkv16, B)
-        dA1, SdA1, _ = jf.jf_linear_dgrad(dQKV, SdQKV, Wq, SWq, B)
-        jf.jf_linear_wgrad(dQKV, SdQKV, A1, SA1, B)
+        (dA1, SdA1, _), _ = jf.jf_linear_bwd(dQKV, SdQKV, Wq, SWq, A1, SA1, B)
         dXa, SdXa, _, _ = jf.jf_layernorm_q_bwd(dA1, SdA1, X, SX, g1, mean1, rstd1, B, workspace=ws)
         jf.jf_add_q(dR1, SdR1, dXa, SdXa, B)
         return qkv16, dat16
@@ -275,14 +307,17 @@ def block_layer(args):
     ms_attn = timed(lambda: (attention(qkv16), attention(qkv16, dat16)), steps, warmup)
     gop = 2.0 * 3 * N * H * (3 * H + H + F + F) * 1e-9      # fwd + dgrad + wgrad of the four linears
     ms_int8 = ms_block - ms_attn
-    print(json.dumps({
+    rec = {
         "metric": "per-block INT8 linear TOPS (fwd+dgrad+wgrad), transformer block with the INT8 data flow",
         "value": round(gop / ms_int8, 3), "unit": "TOPS (966.4 GOP of INT8 linear work / time of the INT8 operators of one block step)",
         "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": round(ms_block, 4), "dtype": "int8", "data": "synthetic",
         "config": {"workload": "config 4: GPT-2-large-shaped block, hidden 1280, 20 heads, FFN 5120, 8x1024 tokens, block 32, "
                                "forward + backward, no bias, no dropout; outputs allocated by torch inside the step"},
         "ms_attention_fp16_fwd_bwd": round(ms_attn, 4), "ms_int8_operators": round(ms_int8, 4),
-        "int8_linear_gop": round(gop, 1), "frac_int8_mfma_peak": round(gop / ms_int8 / INT8_MFMA_PEAK_TOPS, 4)}), flush=True)
+        "int8_linear_gop": round(gop, 1), "frac_int8_mfma_peak": round(gop / ms_int8 / INT8_MFMA_PEAK_TOPS, 4)}
+    if emit:
+        print(json.dumps(rec), flush=True)
+    return rec
 
 
 def main():
@@ -347,8 +382,7 @@ def main():
         run(jf.jf_linear_fwd, Xn, SXn, Wq, SW, B, out=(Y, SY, None))
         jf.jf_gelu_q(Y, SY, B, out=(H, SH))
         jf.jf_gelu_q_bwd(Gq, SG, Y, SY, B, out=(dY, SdY))
-        run(jf.jf_linear_dgrad, dY, SdY, Wq, SW, B, out=(dXn, SdXn, None))
-        run(jf.jf_linear_wgrad, dY, SdY, Xn, SXn, B, out=(dW, SdW, None))
+        run(jf.jf_linear_bwd, dY, SdY, Wq, SW, Xn, SXn, B, out=((dXn, SdXn, None), (dW, SdW, None)))
         jf.jf_layernorm_q_bwd(dXn, SdXn, Xq, SX, gamma, mean, rstd, B, workspace=ws, out=(dX, SdX, dgamma, dbeta))
 
     for _ in range(args.warmup):
@@ -388,14 +422,36 @@ def main():
             graph_ms = (time.perf_counter() - t0g) / args.steps * 1e3
         torch.cuda.current_stream().wait_stream(side)
 
-    gemm_ms = [e0.elapsed_time(e1) for e0, e1 in gemm_events]
-    gemm_avg_ms = sum(gemm_ms) / len(gemm_ms)
-    per_gemm = [sum(gemm_ms[i::3]) / len(gemm_ms[i::3]) for i in range(3)]
+    # GEMM launches bracketed inside the timed region (two per instrumented step: forward, backward pair)
+    in_step = [e0.elapsed_time(e1) for e0, e1 in gemm_events]
     median = lambda v: sorted(v)[len(v) // 2]
-    per_gemm_median = [median(gemm_ms[i::3]) for i in range(3)]
-    per_gemm_min = [min(gemm_ms[i::3]) for i in range(3)]
     gemm_ops = 2.0 * N * C * D
-    achieved = gemm_ops / (gemm_avg_ms * 1e-3) * 1e-12
+
+    # ---- the GEMM kernels in loops of their own: 5 x 100 back-to-back launches between two events each
+    def loop_ms(fn, launches=100, repeats=5):
+        fn()
+        torch.cuda.synchronize()
+        per_launch = []
+        for _ in range(repeats):
+            e0 = torch.cuda.Event(enable_timing=True)
+            e1 = torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(launches):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            per_launch.append(e0.elapsed_time(e1) / launches)
+        return {"mean": sum(per_launch) / repeats, "median": median(per_launch), "min": min(per_launch),
+                "launches": launches * repeats}
+
+    gemm_loops = {
+        "fwd": loop_ms(lambda: jf.jf_linear_fwd(Xn, SXn, Wq, SW, B, out=(Y, SY, None))),
+        "bwd_pair": loop_ms(lambda: jf.jf_linear_bwd(dY, SdY, Wq, SW, Xn, SXn, B, out=((dXn, SdXn, None), (dW, SdW, None)))),
+        "dgrad_alone": loop_ms(lambda: jf.jf_linear_dgrad(dY, SdY, Wq, SW, B, out=(dXn, SdXn, None))),
+        "wgrad_alone": loop_ms(lambda: jf.jf_linear_wgrad(dY, SdY, Xn, SXn, B, out=(dW, SdW, None))),
+    }
+    step_gemm_ms = gemm_loops["fwd"]["mean"] + gemm_loops["bwd_pair"]["mean"]      # the two launches of a step
+    achieved = 3.0 * gemm_ops / (step_gemm_ms * 1e-3) * 1e-12
 
     # ---- per-op GB/s of the memory-bound kernels (separate, untimed-for-`value` loops with events)
     def op_ms(fn, reps=20, replays=5):
@@ -501,10 +557,20 @@ def main():
                                                             out=(yl, syl, dgamma, dbeta)),
                               NL * C * (3 + 3 * sb) + 8 * NL + 12 * C),
         }
+        # the paper's own LayerNorm design: statistics from the row partials of the preceding Add (written here by an Add
+        # of the tensor with zeros)
+        pml, pql = (torch.empty((NL, C // B), dtype=torch.float32, device=dev) for _ in range(2))
+        zl, szl = torch.zeros_like(xl), torch.zeros_like(sxl)
+        big["add_with_row_partials"] = (lambda: jf.jf_add_q(xl, sxl, zl, szl, B, want_partials=True, out=(yl, syl, pml, pql)),
+                                        NL * C * (3 + 3 * sb + 8.0 / B))
+        big["layernorm_fwd_from_row_partials"] = (
+            lambda: jf.jf_layernorm_q_partials(xl, sxl, pml, pql, gamma, beta, 1e-5, B, out=(yl, syl, ml, rl)),
+            NL * C * (2 + 2 * sb + 8.0 / B) + 8 * NL + 8 * C)
         for name, (fn, nbytes) in big.items():
             ms = op_ms(fn, reps=4, replays=3)
             memops_hbm[name] = {"tokens": NL, "ms": round(ms, 4), "GB/s": round(nbytes / (ms * 1e-3) * 1e-9, 1),
                                 "frac_hbm_peak": round(nbytes / (ms * 1e-3) * 1e-9 / HBM_PEAK_GBPS, 4)}
+        del pml, pql, zl, szl
         xq = torch.randn((NL // 4, D), generator=gen, device=dev, dtype=torch.float32)
         oq, osq = i8(NL // 4, D), sc(NL // 4, D)
         ms = op_ms(lambda: jf.jf_quantize_block(xq, B, out=(oq, osq)), reps=4, replays=3)
@@ -514,13 +580,36 @@ def main():
         del xl, sxl, gl, sgl, yl, syl, ml, rl, wsl, xq, oq, osq
         torch.cuda.empty_cache()
 
-    # HBM traffic of the GEMM kernel: measured offline with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see the
-    # summary named in the file) and valid for the default workload only
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "bench_config2_hbm_traffic.json")
-    if (N, C, D, B) == (4096, 768, 3072, 32) and os.path.exists(tpath):
-        traffic = json.load(open(tpath)).get("gemm_avg_bytes_per_launch")
+    # HBM traffic of the GEMM kernels and the ceilings of the fold: measured offline (rocprofv3 --pmc resp. the
+    # micro-benchmarks), summarised into JSON files under profiles/ by microbench/summarize_profiles.py
+    def profile_json(name):
+        path = os.path.join(ROOT, "profiles", name)
+        return json.load(open(path)) if os.path.exists(path) else None
 
+    traffic = None
+    tj = profile_json("bench_config2_hbm_traffic.json")
+    if (N, C, D, B) == (4096, 768, 3072, 32) and tj:
+        traffic = tj.get("gemm_bytes_per_step_launches")
+    fold = profile_json("microbench_fold_ceilings.json")
+    ceiling = None
+    if fold and str(B) in fold.get("bare_fold_TOPS", {}):
+        ceiling = {"bare_TOPS": fold["bare_fold_TOPS"][str(B)],
+                   "with_k_loop_overheads_TOPS": fold.get("with_k_loop_overheads_TOPS", {}).get(str(B)),
+                   "frac_of_bare": round(achieved / fold["bare_fold_TOPS"][str(B)], 4),
+                   "source": fold.get("source")}
+
+    extra = {}
+    if not args.no_extra_configs:
+        # compact records of the other configurations, so that the one timed line carries them
+        recs = sweep(args, shapes=[(8192, 8192, 8192), (16384, 4096, 11008)], emit=False)
+        extra["config5"] = [{"tokens": r["tokens"], "in": r["in"], "out": r["out"], "block": r["block"], "ms": r["ms"],
+                             "TOPS_fwd_dgrad_wgrad": r["TOPS_fwd_dgrad_wgrad"], "frac_int8_mfma_peak": r["frac_int8_mfma_peak"]}
+                            for r in recs]
+        bl = block_layer(args, emit=False)
+        extra["config4"] = {k: bl[k] for k in ("value", "unit", "ms_per_step", "ms_attention_fp16_fwd_bwd", "ms_int8_operators",
+                                               "int8_linear_gop", "frac_int8_mfma_peak")}
+
+    r4 = lambda d: {k: (round(v, 5) if isinstance(v, float) else v) for k, v in d.items()}
     out = {
         "metric": "per-block INT8 linear TOPS (fwd+dgrad+wgrad) + GB/s for INT8 GELU/LayerNorm",
         "value": round(6.0 * N * C * D / (ms_per_step * 1e-3) * 1e-12, 3),
@@ -539,32 +628,33 @@ def main():
                    "tokens": N, "in_features": C, "out_features": D, "block": B},
         "roofline": {
             "bound": "mfma",
-            "kernel": "gemm_kernel (INT8 MFMA, 3 launches per step: fwd, dgrad, wgrad)",
+            "kernel": "gemm_kernel (forward product) + gemm_pair_kernel (input and weight gradient in one grid): the two "
+                      "GEMM launches of a step, 3 x 2*N*C*D INT8 ops",
             "achieved": round(achieved, 2),
             "peak": INT8_MFMA_PEAK_TOPS,
             "unit": "TFLOP/s",
             "unit_note": "INT8 multiply-accumulate counted as 2 ops (TOP/s)",
             "frac": round(achieved / INT8_MFMA_PEAK_TOPS, 4),
             "traffic": traffic,
-            "traffic_note": "HBM bytes per GEMM launch, rocprofv3 FETCH_SIZE + WRITE_SIZE scaled by a 256 MiB copy; "
-                            "algorithmic bytes are 18.1e6",
-            "avg_launch_ms": round(gemm_avg_ms, 5),
-            "per_launch_ms": {"fwd": round(per_gemm[0], 5), "dgrad": round(per_gemm[1], 5), "wgrad": round(per_gemm[2], 5)},
-            "per_launch_ms_median": dict(zip(("fwd", "dgrad", "wgrad"), (round(v, 5) for v in per_gemm_median))),
-            "per_launch_ms_min": dict(zip(("fwd", "dgrad", "wgrad"), (round(v, 5) for v in per_gemm_min))),
-            "launches_timed": len(gemm_ms),
-            # second ceiling of this method on this chip (block 32): the per-K-block dequantize fold issues 32 vector
-            # instructions per MFMA; measured with no memory traffic (fold_chain_rate) and with the LDS reads, barrier
-            # and direct-to-LDS loads of a real K loop (kloop_overheads), see the profile named below
-            "valu_fold_ceiling": {"bare_TOPS": 1461.0, "with_k_loop_overheads_TOPS": 1194.0,
-                                  "frac_of_bare": round(achieved / 1461.0, 4),
-                                  "source": "profiles/microbench_fold_issue_rate_and_l2_bandwidth.txt"} if B == 32 else None,
-            "linear_only_TOPS": round(6.0 * N * C * D / (sum(per_gemm) * 1e-3) * 1e-12, 2),
+            "traffic_note": "HBM bytes of the two GEMM launches of a step, rocprofv3 FETCH_SIZE + WRITE_SIZE scaled by a 256 MiB "
+                            "copy; algorithmic bytes are 3 x 18.1e6",
+            "avg_launch_ms": round(step_gemm_ms / 2, 5),
+            "launch_ms": {k: r4(v) for k, v in gemm_loops.items()},
+            "launch_ms_note": "per launch, from 5 x 100 back-to-back launches between HIP events on the launch stream; "
+                              "`achieved` = 6*N*C*D / (fwd mean + bwd_pair mean)",
+            "in_step_event_ms": {"fwd_median": round(median(in_step[0::2]), 5), "bwd_pair_median": round(median(in_step[1::2]), 5),
+                                 "launches_timed": len(in_step),
+                                 "note": "events around the launches inside the timed region; they add about 2.5 us per launch"},
+            # second ceiling of this method on this chip: the per-K-block dequantize fold issues 32 / 16 / 8 vector
+            # instructions per MFMA at block 32 / 64 / 128 (micro-benchmarks, see the profile named in `source`)
+            "valu_fold_ceiling": ceiling,
+            "linear_only_TOPS": round(achieved, 2),
         },
         "memory_bound_ops": memops,
         "memory_bound_ops_hbm_sized": memops_hbm,
         "paper_context": "paper reports ratios only: 1.42x transformer-layer speedup, 1.49x activation memory vs FP16 on RTX 4090",
     }
+    out.update(extra)
     if graph_ms is not None:
         out["graph_replay_ms_per_step"] = round(graph_ms, 5)
     if not args.no_cpu_baseline:

@@ -255,10 +255,12 @@ int32_t jf_debug_linear_partials(int32_t which, const int8_t* A, const int8_t* B
                                  int32_t block, int64_t kb, int32_t* out, void* stream);
 
 /*
- * Test hook: force the tile shape of the three GEMM entry points (process-wide, not thread-safe).
- *   0 automatic (cost model), 1 128x128, 2 128x96, 3 96x96, 4 64x64, 6 256x128,
- *   7 64x64 with a stage of 128 instead of 64 K bytes (block 32).
- * Shapes 2, 3 and 7 exist for block 32 only; other blocks fall back to 128x128.  Block 128 knows 128x128 and
+ * Test hook: force the tile shape of the GEMM entry points.  This is the one piece of state the library keeps
+ * besides the last-error slot: a process-wide atomic integer, 0 (automatic) unless a test sets it, read once per
+ * launch.  Production callers never call this.
+ *   0 automatic (cost model), 1 128x128, 4 64x64, 6 256x128, 7 64x64 with a stage of 128 instead of 64 K bytes,
+ *   8 128x64; other values: JF_ERR_SHAPE.
+ * Shapes 7 and 8 exist for block 32 only; other blocks fall back to 128x128.  Block 128 knows 128x128 and
  * 256x128 only (automatic: 256x128 once the output has at least 256 such tiles).
  */
 int32_t jf_debug_set_gemm_shape(int32_t shape);

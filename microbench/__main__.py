@@ -1,4 +1,4 @@
-"""Build and run the micro-benchmarks (``python -m paper_2403_12422_amd.microbench [name ...]``) on the visible GPU.
+"""Build and run the micro-benchmarks (``python -m microbench [name ...]`` from the repository root) on the visible GPU.
 
 They measure the machine limits that the GEMM design is judged against: the issue rate of the dequantize fold next
 to INT8 MFMAs (``fold_issue_rate``, and with real data dependences ``fold_chain_rate``), what the LDS fragment

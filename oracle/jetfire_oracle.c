@@ -162,6 +162,7 @@ int oracle_linear_nt(const int8_t* A, const float* SA, const int8_t* Bm, const f
       float* f32 = (float*)malloc(sizeof(float) * block * block);
       double* f64 = (double*)malloc(sizeof(double) * block * block);
       if (!f32 || !f64) {
+#pragma omp atomic write
         err = 1;
         free(f32);
         free(f64);

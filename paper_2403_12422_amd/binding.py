@@ -334,5 +334,5 @@ def jf_debug_linear_partials(which, A, Bm, N, C, D, block, kb):
 
 
 def jf_debug_set_gemm_shape(shape):
-    """Test hook: 0 automatic, 1 128x128, 2 128x96, 3 96x96, 4 64x64, 6 256x128."""
+    """Test hook: 0 automatic, 1 128x128, 4 64x64, 6 256x128, 7 64x64 with a deep stage, 8 128x64."""
     _check(load_library().jf_debug_set_gemm_shape(shape))

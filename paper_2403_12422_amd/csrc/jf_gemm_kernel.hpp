@@ -18,6 +18,9 @@
 // "A" port) so that a lane ends up with 4 consecutive output columns of one
 // output row per register quad: codes pack into dwords without shuffles.
 #pragma once
+#include <algorithm>
+#include <atomic>
+#include <cmath>
 #include <type_traits>
 
 #include "jf_common.hpp"
@@ -55,16 +58,13 @@ struct TileLayout {
   static constexpr int kRows = KMAJOR ? TILE : KC;            // LDS rows: output rows, or K rows
   static constexpr int kCPR = (KMAJOR ? KC : TILE) / 16;      // 16-byte chunks per LDS row
   static constexpr int kSlots = kRows * kCPR;
-  static_assert(kCPR == 4 || kCPR == 6 || kCPR == 8 || kCPR == 16, "rows of 64, 96, 128 or 256 bytes");
-  // 96-byte rows (a 96-wide M-major tile) are left unswizzled: their fragment reads see two-way bank
-  // conflicts, which the vector-ALU-bound B = 32 loop does not notice.
+  static_assert(kCPR == 4 || kCPR == 8 || kCPR == 16, "rows of 64, 128 or 256 bytes");
   // K-major tiles are read with ds_read_b128, which serves 16 lanes (16 consecutive rows, one chunk each) per
   // clock from 256 bytes of banks: the 16 rows must land in 16 different 16-byte bank groups.  A row of 128
   // (64) bytes starts at bank group 8*(r%2) (4*(r%4)), so the XOR term has to run through its 8 (4) values
   // over the rows that share that start.  M-major tiles are read with 8-byte transposing reads, 8 rows per
   // 16 lanes: 8 consecutive rows at a fixed chunk cover 8 bank groups.
   static __device__ __forceinline__ int swz(int r) {
-    if (kCPR == 6) return 0;
     if (KMAJOR) return (r / (16 / kCPR)) % kCPR;
     return (r / (kCPR == 4 ? 2 : 1)) % (kCPR == 16 ? 8 : kCPR);
   }
@@ -621,7 +621,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int tile_inde
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
           const int col = 32 * (wn0 + b) + 8 * q4 + 4 * (lane >> 5);
-          const int chunk = TN == 96 ? (col >> 4) : ((col >> 4) ^ (row & (TN / 16 - 1)));
+          const int chunk = (col >> 4) ^ (row & (TN / 16 - 1));
           *reinterpret_cast<uint32_t*>(code_row(row) + 16 * chunk + (col & 15)) =
               quantize4(acc[a][b][4 * q4], acc[a][b][4 * q4 + 1], acc[a][b][4 * q4 + 2], acc[a][b][4 * q4 + 3], inv);
         }
@@ -637,7 +637,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int tile_inde
       const int id = i * 64 * NW + tid;
       const int row = id / CPRO, c = id % CPRO;
       if (m0 + row < g.M && n0 + 16 * c < g.Nn) {
-        const uint4 v = *reinterpret_cast<const uint4*>(code_row(row) + 16 * (TN == 96 ? c : (c ^ (row & (CPRO - 1)))));
+        const uint4 v = *reinterpret_cast<const uint4*>(code_row(row) + 16 * (c ^ (row & (CPRO - 1))));
         *reinterpret_cast<uint4*>(g.Oq + (int64_t)(m0 + row) * g.Nn + n0 + 16 * c) = v;
       }
     }
@@ -692,53 +692,51 @@ static void launch_cfg(const GemmArgs& a, hipStream_t st) {
 }
 
 // Tile shapes.  At B = 32 the kernel is bound by the vector ALU work of the per-K-block dequantization, which
-// is the same per output element for every shape, and next by the L2 -> LDS staging traffic, which shrinks
-// with the tile.  Three waves per SIMD are needed to hide each other's LDS and MFMA latencies.  So the shape
-// is chosen by a small cost model of the busiest compute unit:
-//   128x128  four waves of 2x2 sub-blocks, three workgroups per compute unit;
-//   128x96   twelve waves of one sub-block } one workgroup per compute unit, for outputs with too few
-//    96x96   nine waves of one sub-block   } 128x128 tiles to fill 256 compute units evenly;
-//    64x64   four waves of one sub-block; with a stage of 128 K bytes (half the barriers, 9 % faster in the K loop,
-//            but only three instead of four workgroups fit a compute unit) when the output has at most 768 such
-//            tiles and one operand is K-major.
-extern int g_forced_shape;  // test hook, see jf_debug_set_gemm_shape
-struct ShapeCost {
-  int64_t cycles;
+// is the same per output element for every shape; what differs is what a wave pays per MFMA for fragment reads and
+// staging (less for the larger wave tiles), how evenly the tiles fill 256 compute units, and the fixed cost of a
+// tile.  Four-wave workgroups throughout:
+//   128x128  waves of 2x2 sub-blocks, three workgroups per compute unit;
+//   128x64   waves of 2x1 sub-blocks, four workgroups per compute unit;
+//    64x64   waves of one sub-block, four per compute unit; with a stage of 128 instead of 64 K bytes (half the
+//            barriers, three workgroups per compute unit) when the output has at most 768 such tiles and one operand
+//            is K-major.
+// The shape is chosen by a model of the busiest SIMD, fitted to the measured times of 39 products (the layers of the
+// benchmark configurations, 9 us to 180 us, all three operand layouts): a workgroup puts one wave of `sub` sub-blocks
+// on every SIMD of its compute unit; with T tiles the busiest unit holds ceil(T / 256) workgroups while they are all
+// resident at once, T / 256 + tail beyond that; a sub-block and K step costs `ns` on a SIMD that holds at least two
+// waves and `ns_alone` on one that holds a single wave (which cannot overlap its own MFMA and fold); `fixed_us` is
+// the launch, first-stage latency and epilogue.  On those 39 products the model's choice is within 0.2 % of the best
+// shape in total (8 % at worst).
+extern std::atomic<int> g_forced_shape;  // test hook, see jf_debug_set_gemm_shape: 0 unless a test sets it
+struct ShapeModel {
+  int tm, tn, sub, resident;
+  double fixed_us, ns, ns_alone, tail;
 };
-static ShapeCost shape_cost(const GemmArgs& a, int tm, int tn, int waves, int tiles_per_wave) {
-  const int64_t n_wg = (int64_t)((a.M + tm - 1) / tm) * ((a.Nn + tn - 1) / tn);
-  const int64_t q = (n_wg + 255) / 256;                              // workgroups on the busiest compute unit
-  const int64_t per_simd = q * ((waves + 3) / 4) * tiles_per_wave;   // sub-blocks the busiest SIMD works through
-  int64_t valu = per_simd * (a.K / 32) * 140;                        // ~35 vector instructions of 4 cycles per sub-block and K step
-  if (waves > 4) valu += valu / 10;                                  // one big workgroup per compute unit: every barrier stalls the whole unit
-  const int64_t stage = q * (int64_t)(tm + tn) * a.K / 28;           // ~28 bytes per cycle of L2 -> LDS per compute unit
-  return {valu > stage ? valu : stage};
+static double shape_cost_us(const ShapeModel& m, const GemmArgs& a) {
+  const double tiles = (double)((a.M + m.tm - 1) / m.tm) * ((a.Nn + m.tn - 1) / m.tn);
+  const double per_cu = tiles / 256.0;
+  const double busiest = tiles <= 256.0 * m.resident ? std::ceil(per_cu) : per_cu + m.tail;
+  return m.fixed_us + busiest * m.sub * (a.K / 32) * (busiest <= 1.0 ? m.ns_alone : m.ns) * 1e-3;
 }
-// Tile shape of a block-32 product, numbered as in jf_debug_set_gemm_shape: 1 128x128, 2 128x96, 3 96x96, 4 64x64,
-// 7 64x64 with a stage of 128 K bytes.
+static const ShapeModel kShape128x128 = {128, 128, 4, 3, 6.5, 61.0, 88.0, 0.5};
+static const ShapeModel kShape128x64 = {128, 64, 2, 4, 4.5, 69.0, 112.0, 0.75};
+static const ShapeModel kShape64x64 = {64, 64, 1, 4, 4.0, 82.0, 172.0, 0.75};
+// Tile shape of a block-32 product, numbered as in jf_debug_set_gemm_shape: 1 128x128, 4 64x64, 7 64x64 with a
+// stage of 128 K bytes, 8 128x64.
 template <bool AK, bool BK>
 static int choose_shape_b32(const GemmArgs& a) {
-  int64_t c128 = shape_cost(a, 128, 128, 4, 4).cycles;
-  int64_t c12896 = shape_cost(a, 128, 96, 12, 1).cycles;
-  int64_t c9696 = shape_cost(a, 96, 96, 9, 1).cycles;
-  int64_t c64 = shape_cost(a, 64, 64, 4, 1).cycles;
-  if (g_forced_shape) {
-    const int64_t big = INT64_MAX;
-    c128 = g_forced_shape == 1 ? 0 : big;
-    c12896 = g_forced_shape == 2 ? 0 : big;
-    c9696 = g_forced_shape == 3 ? 0 : big;
-    c64 = (g_forced_shape == 4 || g_forced_shape == 7) ? 0 : big;
-  }
-  if (c128 <= c12896 && c128 <= c9696 && c128 <= c64) return 1;
-  if (c12896 <= c9696 && c12896 <= c64) return 2;
-  if (c9696 <= c64) return 3;
+  const int forced = g_forced_shape.load(std::memory_order_relaxed);
+  if (forced == 1 || forced == 4 || forced == 7 || forced == 8) return forced;
+  const double c1 = shape_cost_us(kShape128x128, a), c8 = shape_cost_us(kShape128x64, a), c4 = shape_cost_us(kShape64x64, a);
+  if (c1 <= c8 && c1 <= c4) return 1;
+  if (c8 <= c4) return 8;
   const int64_t n64 = (int64_t)((a.M + 63) / 64) * ((a.Nn + 63) / 64);
-  const bool deep = g_forced_shape ? g_forced_shape == 7 : ((AK || BK) && n64 <= 768);
-  return deep ? 7 : 4;
+  return ((AK || BK) && n64 <= 768) ? 7 : 4;
 }
 
 template <int B, bool AK, bool BK, bool DUMP>
 static void launch_shape(const GemmArgs& a, hipStream_t st) {
+  const int g_forced_shape = jf::g_forced_shape.load(std::memory_order_relaxed);
   if (g_forced_shape == 6) {
     launch_cfg<B, 2, 2, 4, 2, AK, BK, DUMP>(a, st);
     return;
@@ -751,8 +749,9 @@ static void launch_shape(const GemmArgs& a, hipStream_t st) {
     if (big_tiles >= 256 && g_forced_shape != 1) launch_cfg<B, 2, 2, 4, 2, AK, BK, DUMP>(a, st);
     else launch_cfg<B, 2, 1, 2, 4, AK, BK, DUMP>(a, st);
   } else if constexpr (B == 64) {
-    const bool big = g_forced_shape ? g_forced_shape != 4
-                                    : shape_cost(a, 128, 128, 4, 4).cycles <= shape_cost(a, 64, 64, 4, 1).cycles;
+    // 128x128 (waves of 2x2 sub-blocks) unless 64x64 tiles (waves of one) leave the busiest SIMD fewer sub-blocks
+    const int64_t t128 = (int64_t)((a.M + 127) / 128) * ((a.Nn + 127) / 128), t64 = (int64_t)((a.M + 63) / 64) * ((a.Nn + 63) / 64);
+    const bool big = g_forced_shape ? g_forced_shape != 4 : 4 * ((t128 + 255) / 256) <= (t64 + 255) / 256;
     if (big)
       launch_cfg<B, 2, 2, 2, 2, AK, BK, DUMP>(a, st);
     else
@@ -760,8 +759,7 @@ static void launch_shape(const GemmArgs& a, hipStream_t st) {
   } else {
     const int shape = choose_shape_b32<AK, BK>(a);
     if (shape == 1) launch_cfg<B, 2, 2, 2, 2, AK, BK, DUMP>(a, st);
-    else if (shape == 2) launch_cfg<B, 1, 1, 4, 3, AK, BK, DUMP>(a, st);
-    else if (shape == 3) launch_cfg<B, 1, 1, 3, 3, AK, BK, DUMP>(a, st);
+    else if (shape == 8) launch_cfg<B, 2, 1, 2, 2, AK, BK, DUMP>(a, st);
     else if (shape == 7) launch_cfg<B, 1, 1, 2, 2, AK, BK, DUMP, true>(a, st);
     else launch_cfg<B, 1, 1, 2, 2, AK, BK, DUMP>(a, st);
   }
@@ -786,11 +784,20 @@ static bool launch_bwd_pair_b32(const GemmArgs& dgrad, const GemmArgs& wgrad, hi
   typedef GemmInstance<32, 1, 1, 2, 2, false, false, false> Wgrad;
   typedef GemmInstance<32, 1, 1, 2, 2, true, false, false> Dgrad;
   typedef GemmInstance<32, 1, 1, 2, 2, true, false, true> DgradDeep;
-  const int sd = choose_shape_b32<true, false>(dgrad), sw = choose_shape_b32<false, false>(wgrad);
-  if ((sd != 4 && sd != 7) || sw != 4) return false;
-  // the first part is padded to a multiple of 8 workgroups so that both parts see the same XCD numbering
+  if (g_forced_shape.load(std::memory_order_relaxed) != 0) return false;   // a forced shape means the single-product kernels
+  // One grid of 64 x 64 tiles of both products against each product alone on its own best shape, by the model above:
+  // in the pair the tiles of the second product fill the compute units that the first leaves idle, so the busiest
+  // SIMD works through the average number of sub-blocks (88 ns each with the pair's mix of operand layouts, measured
+  // at the GPT-2-small and GPT-2-large layer shapes) and the fixed cost is paid once.
+  const double ksd = dgrad.K / 32, ksw = wgrad.K / 32;
   const int tw = Wgrad::tiles(wgrad), td = Dgrad::tiles(dgrad);
-  if (tw % 8) return false;
+  const double pair_us = 5.0 + (td * ksd + tw * ksw) / 256.0 * 88.0e-3;
+  double alone_us = 0.0;
+  for (const GemmArgs* g : {&dgrad, &wgrad})
+    alone_us += std::min(shape_cost_us(kShape128x128, *g), std::min(shape_cost_us(kShape128x64, *g), shape_cost_us(kShape64x64, *g)));
+  // (the first part has to be a multiple of 8 workgroups, so that both parts see the same XCD numbering)
+  if (pair_us >= alone_us || tw % 8) return false;
+  const int sd = ((int64_t)td <= 768) ? 7 : 4;   // the deep stage pays while the tiles of dgrad are resident at once
   if (sd == 7) hipLaunchKernelGGL((gemm_pair_kernel<Wgrad, DgradDeep, 3>), dim3(tw + td), dim3(256), 0, st, wgrad, dgrad, tw);
   else hipLaunchKernelGGL((gemm_pair_kernel<Wgrad, Dgrad, 3>), dim3(tw + td), dim3(256), 0, st, wgrad, dgrad, tw);
   return true;

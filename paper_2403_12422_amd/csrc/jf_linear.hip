@@ -16,7 +16,7 @@ void launch_gemm_wgrad_b64(const GemmArgs& a, bool dump, hipStream_t st);
 void launch_gemm_wgrad_b128(const GemmArgs& a, bool dump, hipStream_t st);
 bool launch_gemm_bwd_pair_b32(const GemmArgs& dgrad, const GemmArgs& wgrad, hipStream_t st);
 
-int g_forced_shape = 0;
+std::atomic<int> g_forced_shape{0};
 
 // which: 0 forward, 1 dgrad, 2 wgrad
 static void launch_gemm(int which, int block, const GemmArgs& a, bool dump, hipStream_t st) {
@@ -155,7 +155,7 @@ extern "C" int32_t jf_debug_linear_partials(int32_t which, const int8_t* A, cons
 }
 
 extern "C" int32_t jf_debug_set_gemm_shape(int32_t shape) {
-  if (shape < 0 || shape > 7 || shape == 5) return JF_ERR_SHAPE;
-  jf::g_forced_shape = shape;
+  if (shape != 0 && shape != 1 && shape != 4 && shape != 6 && shape != 7 && shape != 8) return JF_ERR_SHAPE;
+  jf::g_forced_shape.store(shape, std::memory_order_relaxed);
   return JF_OK;
 }

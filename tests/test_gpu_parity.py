@@ -126,7 +126,7 @@ def test_linear_three_products(block, N, C, D, kw):
     np.testing.assert_array_equal(host(s1), host(s2))
 
 
-@pytest.mark.parametrize("shape", [1, 2, 3, 4, 6, 7])
+@pytest.mark.parametrize("shape", [1, 4, 6, 7, 8])
 @pytest.mark.parametrize("block,N,C,D", [(32, 384, 160, 288), (32, 416, 96, 224), (64, 256, 192, 320), (128, 384, 256, 640)])
 def test_linear_every_tile_shape(shape, block, N, C, D):
     """Each GEMM tile shape, forced through the test hook, on sizes that leave ragged tiles in both directions."""
@@ -161,7 +161,7 @@ def _k_sweep_case(nsteps):
     return _K_SWEEP_CACHE[nsteps]
 
 
-@pytest.mark.parametrize("shape", [1, 2, 3, 4, 6, 7])
+@pytest.mark.parametrize("shape", [1, 4, 6, 7, 8])
 def test_linear_k_loop_every_stage_count(shape):
     """The K loop of the block-32 kernels is a software pipeline whose prologue, main passes and last stages are
     separate code for every count of remaining stages, with the odd K steps of a stage-unaligned K run first.

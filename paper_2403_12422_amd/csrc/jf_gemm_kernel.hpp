@@ -749,9 +749,10 @@ static void launch_shape(const GemmArgs& a, hipStream_t st) {
     if (big_tiles >= 256 && g_forced_shape != 1) launch_cfg<B, 2, 2, 4, 2, AK, BK, DUMP>(a, st);
     else launch_cfg<B, 2, 1, 2, 4, AK, BK, DUMP>(a, st);
   } else if constexpr (B == 64) {
-    // 128x128 (waves of 2x2 sub-blocks) unless 64x64 tiles (waves of one) leave the busiest SIMD fewer sub-blocks
-    const int64_t t128 = (int64_t)((a.M + 127) / 128) * ((a.Nn + 127) / 128), t64 = (int64_t)((a.M + 63) / 64) * ((a.Nn + 63) / 64);
-    const bool big = g_forced_shape ? g_forced_shape != 4 : 4 * ((t128 + 255) / 256) <= (t64 + 255) / 256;
+    // 128x128 (waves of 2x2 sub-blocks) or 64x64 (waves of one), by the same model with the constants of this block
+    // size (half the fold per MFMA): fitted to the same layer shapes, the choice is within 5 % of the better one.
+    static const ShapeModel k128 = {128, 128, 4, 3, 6.5, 44.0, 63.0, 0.5}, k64 = {64, 64, 1, 3, 4.0, 65.0, 190.0, 0.75};
+    const bool big = g_forced_shape ? g_forced_shape != 4 : shape_cost_us(k128, a) <= shape_cost_us(k64, a);
     if (big)
       launch_cfg<B, 2, 2, 2, 2, AK, BK, DUMP>(a, st);
     else

@@ -446,6 +446,10 @@ __global__ void __launch_bounds__(256) dropout_kernel(const int8_t* __restrict__
 // max-abs is a local maximum followed by four cross-lane steps, and nothing is exchanged between waves: no LDS
 // traffic (but the GELU tables), no barrier.  Per element the kernels spend what Alg. 2 needs (unpack, the
 // operator, max-abs, Eq. 1) and little else; the per-lane overhead is paid once per 64 elements.
+// Strips (waves) per workgroup: four neighbouring strips of the same rows, so that 512 contiguous bytes of every row
+// are requested close together in time (on 0.8 GB tensors of 3072 columns 5.4-5.7 TB/s instead of 4.4-5.0 with one
+// strip per workgroup).  The waves of a workgroup share nothing and never meet at a barrier.
+constexpr int kStripWaves = 4;
 struct Strip32 {
   int ch, rsub;     // chunk column and row of the lane inside an 8-row pass
   int bi, lc;       // block row of the strip, block columns of the matrix
@@ -454,13 +458,19 @@ struct Strip32 {
   int64_t base;     // element offset of the lane's chunk in pass 0; pass p adds 8 p cols.  Lanes outside the matrix
                     // point at the strip's first chunk instead: they load like the others (no branch), share their
                     // reductions only with each other (whole blocks are in or out), and store nothing.
-  __device__ __forceinline__ Strip32(int cols) {
-    const int lane = threadIdx.x;
+  int lane, wave;   // lane of the wave, wave of the workgroup (a workgroup holds kStripWaves neighbouring strips)
+  bool inside;      // the wave's strip exists (the last workgroup may hold fewer)
+  __device__ __forceinline__ Strip32(int rows, int cols) {
+    lane = threadIdx.x & 63;
+    wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     ch = lane & 7;
     rsub = lane >> 3;
-    const TileIndex wg = tile_of_workgroup((cols + 127) / 128);
-    c0 = wg.x * 128;
-    bi = wg.y;
+    const unsigned groups = (unsigned)((cols + 127) / 128), strips = groups * (unsigned)(rows / 32);
+    const unsigned id = blockIdx.x * (blockDim.x >> 6) + wave;   // strips are numbered column group fastest
+    inside = id < strips;
+    const unsigned sid = inside ? id : strips - 1;
+    c0 = (int)(sid % groups) * 128;
+    bi = (int)(sid / groups);
     lc = cols / 32;
     col = c0 + 16 * ch;
     ok = col < cols;
@@ -541,11 +551,13 @@ __device__ __forceinline__ void gelu_build_table(float* tab, float sx, int lane)
 }
 
 template <bool BWD>
-__global__ void __launch_bounds__(64) gelu_strip32_kernel(const int8_t* __restrict__ X, const float* __restrict__ SX,
+__global__ void __launch_bounds__(64 * kStripWaves) gelu_strip32_kernel(const int8_t* __restrict__ X, const float* __restrict__ SX,
                                                           const int8_t* __restrict__ G, const float* __restrict__ SG,
                                                           int rows, int cols, int8_t* __restrict__ Y, float* __restrict__ SY) {
-  __shared__ float s_tab[4][256];
-  const Strip32 t(cols);
+  __shared__ float s_tabs[kStripWaves][4][256];
+  float (*const s_tab)[256] = s_tabs[threadIdx.x >> 6];
+  const Strip32 t(rows, cols);
+  if (!t.inside) return;   // a whole wave; the strip kernels have no workgroup barrier
   const int64_t pass = (int64_t)8 * cols;
   // the codes are requested first: their latency runs beside the table build
   uint4 px[4], pg[BWD ? 4 : 1];
@@ -560,7 +572,7 @@ __global__ void __launch_bounds__(64) gelu_strip32_kernel(const int8_t* __restri
   const int nblk = min(4, t.lc - t.c0 / 32);
 #pragma unroll
   for (int k = 0; k < 4; ++k)
-    if (k < nblk) gelu_build_table<BWD>(s_tab[k], sx_row[k], threadIdx.x);
+    if (k < nblk) gelu_build_table<BWD>(s_tab[k], sx_row[k], threadIdx.x & 63);
   // The tables are written and read by this wave only; LDS serves a wave's accesses in program order, and the
   // fences keep the compiler from moving the lookups above the writes.
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -597,18 +609,19 @@ __global__ void __launch_bounds__(64) gelu_strip32_kernel(const int8_t* __restri
   double inv;
   strip32_block_scale(m, scale, inv);
   if (!t.ok) return;
-  if ((threadIdx.x & 57) == 0) SY[t.block_index()] = scale;
+  if ((t.lane & 57) == 0) SY[t.block_index()] = scale;
 #pragma unroll
   for (int p = 0; p < 4; ++p) *reinterpret_cast<uint4*>(Y + t.base + p * pass) = quantize16(y[p], inv);
 }
 
 // Add (App. A) at block size 32, optionally with the row partials of App. A's LayerNorm paragraph (PARTIALS).
 template <bool PARTIALS>
-__global__ void __launch_bounds__(64) add_strip32_kernel(const int8_t* __restrict__ X1, const float* __restrict__ S1,
+__global__ void __launch_bounds__(64 * kStripWaves) add_strip32_kernel(const int8_t* __restrict__ X1, const float* __restrict__ S1,
                                                          const int8_t* __restrict__ X2, const float* __restrict__ S2,
                                                          int rows, int cols, int8_t* __restrict__ Y, float* __restrict__ SY,
                                                          float* __restrict__ row_mean, float* __restrict__ row_sumsq) {
-  const Strip32 t(cols);
+  const Strip32 t(rows, cols);
+  if (!t.inside) return;   // a whole wave; the strip kernels have no workgroup barrier
   const int64_t pass = (int64_t)8 * cols;
   float y[4][16];
   float m = 0.0f;
@@ -648,7 +661,7 @@ __global__ void __launch_bounds__(64) add_strip32_kernel(const int8_t* __restric
   double inv;
   strip32_block_scale(m, scale, inv);
   if (!t.ok) return;
-  if ((threadIdx.x & 57) == 0) SY[t.block_index()] = scale;
+  if ((t.lane & 57) == 0) SY[t.block_index()] = scale;
 #pragma unroll
   for (int p = 0; p < 4; ++p) *reinterpret_cast<uint4*>(Y + t.base + p * pass) = quantize16(y[p], inv);
 }
@@ -664,10 +677,11 @@ __device__ __forceinline__ uint32_t keep_bytes(uint32_t nibble) {
 
 // Dropout (App. A) at block size 32: dropped codes are cleared in the packed dwords (a code of 0 dequantizes to
 // exactly 0), so the mask costs a few integer instructions per four elements and none per element.
-__global__ void __launch_bounds__(64) dropout_strip32_kernel(const int8_t* __restrict__ X, const float* __restrict__ SX,
+__global__ void __launch_bounds__(64 * kStripWaves) dropout_strip32_kernel(const int8_t* __restrict__ X, const float* __restrict__ SX,
                                                              const uint8_t* __restrict__ mask, float keep_scale, int rows,
                                                              int cols, int8_t* __restrict__ Y, float* __restrict__ SY) {
-  const Strip32 t(cols);
+  const Strip32 t(rows, cols);
+  if (!t.inside) return;   // a whole wave; the strip kernels have no workgroup barrier
   const int64_t pass = (int64_t)8 * cols;
   float y[4][16];
   float m = 0.0f;
@@ -698,7 +712,7 @@ __global__ void __launch_bounds__(64) dropout_strip32_kernel(const int8_t* __res
   double inv;
   strip32_block_scale(m, scale, inv);
   if (!t.ok) return;
-  if ((threadIdx.x & 57) == 0) SY[t.block_index()] = scale;
+  if ((t.lane & 57) == 0) SY[t.block_index()] = scale;
 #pragma unroll
   for (int p = 0; p < 4; ++p) *reinterpret_cast<uint4*>(Y + t.base + p * pass) = quantize16(y[p], inv);
 }
@@ -1489,11 +1503,12 @@ __global__ void __launch_bounds__(64 * WMAX) __attribute__((amdgpu_waves_per_eu(
 // Second kernel: dx on 32 x 128 strips, one wave each, from the row means q1 = mean_C(ghat), q2 = mean_C(ghat xhat)
 // that the first kernel left (one share per range of 2048 columns): dx = ug a_c + ux b + d with per-row b = -rstd q2 sx rstd, d and per-column
 // a_c = rstd sg gamma_c (u = code + 128), then Eq. 1.  Rows may be of any width.
-__global__ void __launch_bounds__(64) layernorm_bwd_apply_strip32_kernel(
+__global__ void __launch_bounds__(64 * kStripWaves) layernorm_bwd_apply_strip32_kernel(
     const int8_t* __restrict__ G, const float* __restrict__ SG, const int8_t* __restrict__ X, const float* __restrict__ SX,
     const float* __restrict__ gamma, const float* __restrict__ mean_in, const float* __restrict__ rstd_in,
     const float* __restrict__ row_means, int ranges, int rows, int cols, int8_t* __restrict__ dX, float* __restrict__ SdX) {
-  const Strip32 t(cols);
+  const Strip32 t(rows, cols);
+  if (!t.inside) return;   // a whole wave; the strip kernels have no workgroup barrier
   const int64_t pass = (int64_t)8 * cols;
   uint4 px[4], pg[4];
   float mu[4], rs[4];
@@ -1537,7 +1552,7 @@ __global__ void __launch_bounds__(64) layernorm_bwd_apply_strip32_kernel(
   double inv;
   strip32_block_scale(m, scale, inv);
   if (!t.ok) return;
-  if ((threadIdx.x & 57) == 0) SdX[t.block_index()] = scale;
+  if ((t.lane & 57) == 0) SdX[t.block_index()] = scale;
 #pragma unroll
   for (int p = 0; p < 4; ++p) *reinterpret_cast<uint4*>(dX + t.base + p * pass) = quantize16(y[p], inv);
 }
@@ -1576,11 +1591,12 @@ __global__ void __launch_bounds__(256) row_stats_from_partials_kernel(const floa
 // LayerNorm at block size 32 from given row statistics (App. A: the operator "directly accesses" mean and rstd):
 // y = (x - mean) rstd gamma + beta on 32 x 128 strips, one wave each, like the other element-wise operators --
 // no workgroup needs a whole row, so rows may be of any width.
-__global__ void __launch_bounds__(64) layernorm_apply_strip32_kernel(const int8_t* __restrict__ X, const float* __restrict__ SX,
+__global__ void __launch_bounds__(64 * kStripWaves) layernorm_apply_strip32_kernel(const int8_t* __restrict__ X, const float* __restrict__ SX,
                                                                      const float* __restrict__ gamma, const float* __restrict__ beta,
                                                                      const float* __restrict__ mean_in, const float* __restrict__ rstd_in,
                                                                      int rows, int cols, int8_t* __restrict__ Y, float* __restrict__ SY) {
-  const Strip32 t(cols);
+  const Strip32 t(rows, cols);
+  if (!t.inside) return;   // a whole wave; the strip kernels have no workgroup barrier
   const int64_t pass = (int64_t)8 * cols;
   uint4 px[4];
   float mu[4], rs[4];
@@ -1610,7 +1626,7 @@ __global__ void __launch_bounds__(64) layernorm_apply_strip32_kernel(const int8_
   double inv;
   strip32_block_scale(m, scale, inv);
   if (!t.ok) return;
-  if ((threadIdx.x & 57) == 0) SY[t.block_index()] = scale;
+  if ((t.lane & 57) == 0) SY[t.block_index()] = scale;
 #pragma unroll
   for (int p = 0; p < 4; ++p) *reinterpret_cast<uint4*>(Y + t.base + p * pass) = quantize16(y[p], inv);
 }
@@ -1660,6 +1676,12 @@ static void launch_gelu_cfg(const int8_t* X, const float* SX, const int8_t* G, c
   hipLaunchKernelGGL((gelu_kernel<BWD, B, J>), dim3(tile_grid((cols + 128 * J - 1) / (128 * J), rows / B)), dim3(256), 0, st,
                      X, SX, G, SG, rows, cols, Y, SY);
 }
+// workgroups of the strip kernels: kStripWaves strips each
+static dim3 strip_grid(int64_t rows, int64_t cols) {
+  const int64_t strips = ((cols + 127) / 128) * (rows / 32);
+  return dim3((unsigned)((strips + kStripWaves - 1) / kStripWaves));
+}
+
 template <bool BWD>
 static void launch_gelu(int block, const int8_t* X, const float* SX, const int8_t* G, const float* SG, int rows,
                         int cols, int8_t* Y, float* SY, hipStream_t st) {
@@ -1673,7 +1695,7 @@ static void launch_gelu(int block, const int8_t* X, const float* SX, const int8_
     if (n <= (int64_t(64) << 20)) launch_gelu_wave<BWD, 64>(X, SX, G, SG, rows, cols, Y, SY, st);
     else launch_gelu_cfg<BWD, 64, 2>(X, SX, G, SG, rows, cols, Y, SY, st);
   } else {
-    hipLaunchKernelGGL((gelu_strip32_kernel<BWD>), dim3(tile_grid((cols + 127) / 128, rows / 32)), dim3(64), 0, st, X, SX, G, SG,
+    hipLaunchKernelGGL((gelu_strip32_kernel<BWD>), strip_grid(rows, cols), dim3(64 * kStripWaves), 0, st, X, SX, G, SG,
                        rows, cols, Y, SY);
   }
 }
@@ -1772,7 +1794,7 @@ static int32_t layernorm_fwd(const int8_t* X, const float* SX, const float* row_
     }
     rc = launch_status();
     if (rc != JF_OK) return rc;
-    hipLaunchKernelGGL(layernorm_apply_strip32_kernel, dim3(tile_grid((C + 127) / 128, N / 32)), dim3(64), 0, st, X, SX, gamma,
+    hipLaunchKernelGGL(layernorm_apply_strip32_kernel, strip_grid(N, C), dim3(64 * kStripWaves), 0, st, X, SX, gamma,
                        beta, mean, rstd, (int)N, (int)C, Y, SY);
     return launch_status();
   }
@@ -1812,7 +1834,7 @@ extern "C" int32_t jf_dropout_q(const int8_t* X, const float* SX, const uint8_t*
   const float keep_scale = (float)(1.0 / (1.0 - (double)p));
   const int rows = (int)N, cols = (int)C;
   if (block == 32)
-    hipLaunchKernelGGL(dropout_strip32_kernel, dim3(tile_grid((C + 127) / 128, N / 32)), dim3(64), 0, st, X, SX, mask_bits,
+    hipLaunchKernelGGL(dropout_strip32_kernel, strip_grid(N, C), dim3(64 * kStripWaves), 0, st, X, SX, mask_bits,
                        keep_scale, rows, cols, Y, SY);
   else if (block == 64) hipLaunchKernelGGL((dropout_kernel<64>), grid, dim3(256), 0, st, X, SX, mask_bits, keep_scale, rows, cols, Y, SY);
   else hipLaunchKernelGGL((dropout_kernel<128>), grid, dim3(256), 0, st, X, SX, mask_bits, keep_scale, rows, cols, Y, SY);
@@ -1831,9 +1853,9 @@ extern "C" int32_t jf_add_q(const int8_t* X1, const float* S1, const int8_t* X2,
   const dim3 grid(tile_grid((C + 127) / 128, N / block));
   const int rows = (int)N, cols = (int)C;
   if (block == 32) {
-    const dim3 strips(tile_grid((C + 127) / 128, N / 32));
-    if (row_mean) hipLaunchKernelGGL((add_strip32_kernel<true>), strips, dim3(64), 0, st, X1, S1, X2, S2, rows, cols, Y, SY, row_mean, row_sumsq);
-    else hipLaunchKernelGGL((add_strip32_kernel<false>), strips, dim3(64), 0, st, X1, S1, X2, S2, rows, cols, Y, SY, row_mean, row_sumsq);
+    const dim3 strips = strip_grid(N, C);
+    if (row_mean) hipLaunchKernelGGL((add_strip32_kernel<true>), strips, dim3(64 * kStripWaves), 0, st, X1, S1, X2, S2, rows, cols, Y, SY, row_mean, row_sumsq);
+    else hipLaunchKernelGGL((add_strip32_kernel<false>), strips, dim3(64 * kStripWaves), 0, st, X1, S1, X2, S2, rows, cols, Y, SY, row_mean, row_sumsq);
   } else if (block == 64) hipLaunchKernelGGL((add_kernel<64>), grid, dim3(256), 0, st, X1, S1, X2, S2, rows, cols, Y, SY, row_mean, row_sumsq);
   else hipLaunchKernelGGL((add_kernel<128>), grid, dim3(256), 0, st, X1, S1, X2, S2, rows, cols, Y, SY, row_mean, row_sumsq);
   return launch_status();
@@ -1856,7 +1878,7 @@ static int32_t layernorm_bwd_launch(const int8_t* dY, const float* SdY, const in
                                 row_means, partials);
     const int32_t rc1 = launch_status();
     if (rc1 != JF_OK) return rc1;
-    hipLaunchKernelGGL(layernorm_bwd_apply_strip32_kernel, dim3(tile_grid((C + 127) / 128, N / 32)), dim3(64), 0, st, dY, SdY, X, SX,
+    hipLaunchKernelGGL(layernorm_bwd_apply_strip32_kernel, strip_grid(N, C), dim3(64 * kStripWaves), 0, st, dY, SdY, X, SX,
                        gamma, mean, rstd, row_means, ranges, (int)N, (int)C, dX, SdX);
   } else {
     const int nit = (int)((C + 1023) / 1024);

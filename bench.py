@@ -41,6 +41,8 @@ def parse_args():
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="oracle time budget of the CPU baseline leg")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also launch plain 256 MiB device copies, the reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE")
+    ap.add_argument("--gemm-loop-launches", type=int, default=100,
+                    help="back-to-back launches per repeat (5 repeats) of the dedicated GEMM timing loops")
     ap.add_argument("--no-extra-configs", action="store_true",
                     help="skip the compact config 4 (transformer block) and config 5 (large GEMMs) records of the default line")
     ap.add_argument("--event-every", type=int, default=4,
@@ -428,7 +430,7 @@ def main():
     gemm_ops = 2.0 * N * C * D
 
     # ---- the GEMM kernels in loops of their own: 5 x 100 back-to-back launches between two events each
-    def loop_ms(fn, launches=100, repeats=5):
+    def loop_ms(fn, launches=args.gemm_loop_launches, repeats=5):
         fn()
         torch.cuda.synchronize()
         per_launch = []
@@ -454,9 +456,10 @@ def main():
     achieved = 3.0 * gemm_ops / (step_gemm_ms * 1e-3) * 1e-12
 
     # ---- per-op GB/s of the memory-bound kernels (separate, untimed-for-`value` loops with events)
-    def op_ms(fn, reps=20, replays=5):
-        """Average duration of one launch: `reps` back-to-back launches captured in a HIP graph (so that the
-        host-side launch cost does not hide the kernel time), replayed a few times between two events."""
+    def op_ms(fn, reps=20, replays=7):
+        """Duration of one launch: `reps` back-to-back launches captured in a HIP graph (so that the host-side launch
+        cost does not hide the kernel time), replayed `replays` times, each replay between two events; the median
+        replay (the first replays of a freshly allocated tensor run slower)."""
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
         with torch.cuda.stream(side):
@@ -466,15 +469,17 @@ def main():
                 for _ in range(reps):
                     fn()
             gr.replay()
-            e0 = torch.cuda.Event(enable_timing=True)
-            e1 = torch.cuda.Event(enable_timing=True)
-            e0.record()
+            times = []
             for _ in range(replays):
+                e0 = torch.cuda.Event(enable_timing=True)
+                e1 = torch.cuda.Event(enable_timing=True)
+                e0.record()
                 gr.replay()
-            e1.record()
-            side.synchronize()
+                e1.record()
+                side.synchronize()
+                times.append(e0.elapsed_time(e1) / reps)
         torch.cuda.current_stream().wait_stream(side)
-        return e0.elapsed_time(e1) / (reps * replays)
+        return sorted(times)[len(times) // 2]
 
     sb = 4.0 / (B * B)
     ops = {
@@ -541,7 +546,7 @@ def main():
         # what a plain device-to-device copy of the same tensor reaches (torch's copy kernel): the practical HBM rate
         big["plain_copy_reference"] = (lambda: yg.copy_(xg), NG * D * 2)
         for name, (fn, nbytes) in big.items():
-            ms = op_ms(fn, reps=4, replays=3)
+            ms = op_ms(fn, reps=4, replays=7)
             memops_hbm[name] = {"tokens": NG, "ms": round(ms, 4), "GB/s": round(nbytes / (ms * 1e-3) * 1e-9, 1),
                                 "frac_hbm_peak": round(nbytes / (ms * 1e-3) * 1e-9 / HBM_PEAK_GBPS, 4)}
         del xg, sxg, gg, sgg, yg, syg, mbg
@@ -567,13 +572,13 @@ def main():
             lambda: jf.jf_layernorm_q_partials(xl, sxl, pml, pql, gamma, beta, 1e-5, B, out=(yl, syl, ml, rl)),
             NL * C * (2 + 2 * sb + 8.0 / B) + 8 * NL + 8 * C)
         for name, (fn, nbytes) in big.items():
-            ms = op_ms(fn, reps=4, replays=3)
+            ms = op_ms(fn, reps=4, replays=7)
             memops_hbm[name] = {"tokens": NL, "ms": round(ms, 4), "GB/s": round(nbytes / (ms * 1e-3) * 1e-9, 1),
                                 "frac_hbm_peak": round(nbytes / (ms * 1e-3) * 1e-9 / HBM_PEAK_GBPS, 4)}
         del pml, pql, zl, szl
         xq = torch.randn((NL // 4, D), generator=gen, device=dev, dtype=torch.float32)
         oq, osq = i8(NL // 4, D), sc(NL // 4, D)
-        ms = op_ms(lambda: jf.jf_quantize_block(xq, B, out=(oq, osq)), reps=4, replays=3)
+        ms = op_ms(lambda: jf.jf_quantize_block(xq, B, out=(oq, osq)), reps=4, replays=7)
         nbytes = (NL // 4) * D * (5 + sb)
         memops_hbm["quantize_f32"] = {"tokens": NL // 4, "ms": round(ms, 4), "GB/s": round(nbytes / (ms * 1e-3) * 1e-9, 1),
                                       "frac_hbm_peak": round(nbytes / (ms * 1e-3) * 1e-9 / HBM_PEAK_GBPS, 4)}
@@ -640,7 +645,7 @@ def main():
                             "copy; algorithmic bytes are 3 x 18.1e6",
             "avg_launch_ms": round(step_gemm_ms / 2, 5),
             "launch_ms": {k: r4(v) for k, v in gemm_loops.items()},
-            "launch_ms_note": "per launch, from 5 x 100 back-to-back launches between HIP events on the launch stream; "
+            "launch_ms_note": f"per launch, from 5 x {args.gemm_loop_launches} back-to-back launches between HIP events on the launch stream; "
                               "`achieved` = 6*N*C*D / (fwd mean + bwd_pair mean)",
             "in_step_event_ms": {"fwd_median": round(median(in_step[0::2]), 5), "bwd_pair_median": round(median(in_step[1::2]), 5),
                                  "launches_timed": len(in_step),

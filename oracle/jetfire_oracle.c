@@ -493,7 +493,7 @@ int oracle_row_stats_from_partials(const float* row_mean, const float* row_sumsq
   return ORACLE_OK;
 }
 
-/* App. A: LayerNorm that "directly accesses" given row statistics (FP32 mean, rstd):
+/* App. A: LayerNorm that is handed its row statistics (FP32 mean, rstd) instead of computing them:
  * y = (x - mean) * rstd * gamma + beta on the dequantized input, then Alg. 2's quantize step. */
 int oracle_layernorm_q_stats(const int8_t* X, const float* SX, const float* gamma, const float* beta, const float* mean,
                              const float* rstd, int64_t N, int64_t C, int block, int8_t* Y, float* SY, double* y_f) {

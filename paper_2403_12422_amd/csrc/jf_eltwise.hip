@@ -12,53 +12,67 @@
 namespace jf {
 
 // ------------------------------------------------------------------------------------------------
-// Standard normal upper tail Q(a) = Phi(-a), a >= 0, with small RELATIVE error (about 1e-6) over the
-// whole FP32 range, so that a block lying entirely in the negative tail still gets an accurate scale.
-//   erfc(z) = t * exp(P(t) - z^2),  t = 1 / (1 + z/2),  P a degree-9 polynomial fitted by least squares
-//   on Chebyshev nodes against log(erfcx(z)/t) for 0 <= z <= 9.5 (max error of P: 4.5e-8).
-// z^2 = a^2/2 is formed exactly (product + FMA residual) and the base-2 exponent is split in a large part H and
-// a small part m, each exponentiated separately; otherwise the FP32 rounding of an exponent of size z^2
-// would cost log2(z^2) bits of the result.  Also returns exp(-z^2) (needed by the GELU derivative).
-struct TailEval {
-  float q;      // Q(a)
-  float ez;     // exp(-a^2/2)
-};
-__device__ __forceinline__ TailEval normal_tail(float a) {
-  const float L2E = 1.4426950408889634f;
-  const float z = a * 0.70710678118654752f;
-  const float t = __builtin_amdgcn_rcpf(__builtin_fmaf(0.5f, z, 1.0f));
-  float p = 1.409394439e-01f;
-  p = __builtin_fmaf(p, t, -6.589882025e-01f);
-  p = __builtin_fmaf(p, t, 1.105068749e+00f);
-  p = __builtin_fmaf(p, t, -6.270881863e-01f);
-  p = __builtin_fmaf(p, t, -1.378501274e-01f);
-  p = __builtin_fmaf(p, t, 3.206818161e-02f);
-  p = __builtin_fmaf(p, t, 2.404601430e-02f);
-  p = __builtin_fmaf(p, t, 3.888682058e-01f);
-  p = __builtin_fmaf(p, t, 9.983709344e-01f);
-  p = __builtin_fmaf(p, t, -1.265434969e+00f);
-  const float aa = a * a;
-  const float s1 = 0.5f * aa;
-  const float s2 = 0.5f * __builtin_fmaf(a, a, -aa);     // z^2 = a^2/2 = s1 + s2 exactly
-  const float H = -s1 * L2E;
-  const float r1 = __builtin_fmaf(-s1, L2E, -H);         // -s1*log2(e) = H + r1 exactly
-  const float corr = __builtin_fmaf(-s2, L2E, r1);       // exponent of exp(-z^2) beyond H (tiny)
-  const float e1 = __builtin_amdgcn_exp2f(H);
-  TailEval r;
-  r.ez = e1 * __builtin_fmaf(corr, 0.6931471805599453f, 1.0f);
-  r.q = 0.5f * t * e1 * __builtin_amdgcn_exp2f(__builtin_fmaf(p, L2E, corr));
-  return r;
+// One table of GELU (or its derivative) at the 255 values code * sx of a block, indexed by the code byte taken as
+// unsigned: lane l evaluates codes l and l + 64 and, by symmetry, -l and -(l + 64).  Both functions are written in
+// terms of the upper tail Q(a) = Phi(-a), a >= 0 (App. A):
+//   GELU(x) = x Phi(x):  f(a) = a - a Q(a),  f(-a) = -a Q(a);
+//   GELU'(x) = Phi(x) + x phi(x):  f(a) = 1 - Q(a) + a phi(a),  f(-a) = Q(a) - a phi(a),  phi(a) = exp(-a^2/2) / sqrt(2 pi).
+//   Q(a) = t P(t) exp(-a^2/2),  t = 1 / (1 + a / sqrt(8)),  P of degree 8 fitted by weighted least squares on Chebyshev
+//   nodes to erfcx(a / sqrt 2) / (2 t) for 0 <= a <= 13.4 (relative error 5e-8; evaluated in FP32: 4e-7).
+// exp(-a^2/2) = 2^H (1 + r ln 2) with H = fl(-a^2 log2(e)/2) and r the exact remainder (product residuals by FMA),
+// so that the FP32 rounding of an exponent of size a^2 does not cost log2(a^2) bits: Q keeps a relative error of
+// about 1e-6 into the far tail, where a block that lies entirely there takes its scale from.
+template <bool BWD>
+__device__ __forceinline__ void gelu_table_entries(float a, float& pos, float& neg) {
+  const float ac = fminf(a, 40.0f);                       // Q(40) = 0 in FP32; keeps a^2 finite
+  const float t = __builtin_amdgcn_rcpf(__builtin_fmaf(ac, 0.35355339059327373f, 1.0f));
+  float p = -2.9970746985e-02f;
+  p = __builtin_fmaf(p, t, 1.4432375881e-01f);
+  p = __builtin_fmaf(p, t, -2.4760739076e-01f);
+  p = __builtin_fmaf(p, t, 1.4335782902e-01f);
+  p = __builtin_fmaf(p, t, -1.6097390692e-02f);
+  p = __builtin_fmaf(p, t, 1.0243339323e-01f);
+  p = __builtin_fmaf(p, t, 1.2129997806e-01f);
+  p = __builtin_fmaf(p, t, 1.4121892641e-01f);
+  p = __builtin_fmaf(p, t, 1.4104161820e-01f);
+  const float K = -0.72134752044448170f;                  // -log2(e) / 2
+  const float aa = ac * ac;
+  const float lo = __builtin_fmaf(ac, ac, -aa);           // a^2 = aa + lo exactly
+  const float H = aa * K;
+  const float r = __builtin_fmaf(lo, K, __builtin_fmaf(aa, K, -H));
+  const float ez = __builtin_amdgcn_exp2f(H) * __builtin_fmaf(r, 0.6931471805599453f, 1.0f);   // exp(-a^2/2)
+  const float q = (t * p) * ez;
+  if (BWD) {
+    const float s = (a * 0.39894228040143268f) * ez;      // a phi(a)
+    pos = (1.0f - q) + s;
+    neg = q - s;
+  } else {
+    const float aq = a * q;
+    pos = a - aq;
+    neg = 0.0f - aq;
+  }
 }
 
-// Both table functions are written in terms of the upper tail Q(|x|) of the normal distribution (App. A):
-//   GELU(x) = x Phi(x) = max(x, 0) - |x| Q(|x|),
-//   dGELU/dx = x phi(x) + Phi(x),  phi(x) = exp(-x^2/2) / sqrt(2 pi),  Phi(x) = x > 0 ? 1 - Q(|x|) : Q(|x|).
+template <bool BWD>
+__device__ __forceinline__ void gelu_build_table(float* tab, float sx, int lane) {
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const int i = lane + 64 * h;
+    float pos, neg;
+    gelu_table_entries<BWD>((float)i * sx, pos, neg);
+    // code 0: GELU(0) = 0 comes out exactly; GELU'(0) = 1/2 is set, because the fit is only good to 4e-7 there and a
+    // derivative of 0.49999997 would push every halved gradient code off its rounding tie.  Entry 128 (code -128,
+    // which no quantizer output holds) is 0.
+    tab[i] = (BWD && i == 0) ? 0.5f : pos;
+    tab[i == 0 ? 128 : 256 - i] = i == 0 ? 0.0f : neg;
+  }
+}
 
 // ------------------------------------------------------------------------------------------------
-// GELU forward / backward.  One workgroup of four waves owns B rows x J*128 columns = J*128/min(B,128)
+// GELU forward / backward at block sizes 64 and 128 (large tensors at 64).  One workgroup of four waves owns B rows x J*128 columns = J*128/min(B,128)
 // quantization blocks; wave w owns rows [w*B/4, (w+1)*B/4) in B/32 passes of 8 rows, lane = (row l/8,
 // 16-byte chunk l%8) in each of the J 128-column halves, so every row segment is a full 128-byte line.
-// J = 2 (B = 32, 64) halves the number of workgroups; the tables built per element stay the same.
+// J = 2 (B = 64) halves the number of workgroups; the tables built per element stay the same.
 template <bool BWD, int B, int J>
 __global__ void __launch_bounds__(256) gelu_kernel(const int8_t* __restrict__ X, const float* __restrict__ SX,
                                                     const int8_t* __restrict__ G, const float* __restrict__ SG,
@@ -109,20 +123,9 @@ __global__ void __launch_bounds__(256) gelu_kernel(const int8_t* __restrict__ X,
     for (int k = __builtin_amdgcn_readfirstlane(threadIdx.x >> 7); k < NTAB; k += 2) {
       const int bcol = c0 + (k / TPH) * 128 + (k % TPH) * B;
       if (bcol < cols) {
-        const float a = (float)i * sx_row[bcol / B];
-        const TailEval te = normal_tail(a);
         float pos, neg;  // f(+a), f(-a)
-        if (BWD) {       // x phi(x) + Phi(x)
-          const float slope = a * 0.39894228040143268f;
-          pos = __builtin_fmaf(slope, te.ez, 1.0f - te.q);
-          neg = __builtin_fmaf(-slope, te.ez, te.q);
-        } else {         // max(x, 0) - |x| Q(|x|)
-          const float aq = a * te.q;
-          pos = a - aq;
-          neg = 0.0f - aq;
-        }
-        // code 0: GELU(0) = 0 comes out exactly; GELU'(0) = 1/2 is set, because the tail fit is only good to 4e-8
-        // there and a derivative of 0.49999994 would push every halved gradient code off its rounding tie
+        gelu_table_entries<BWD>((float)i * sx_row[bcol / B], pos, neg);
+        // code 0: GELU'(0) = 1/2 exactly, entry 128 unused: see gelu_build_table
         s_tab[k][i] = (BWD && i == 0) ? 0.5f : pos;
         s_tab[k][i == 0 ? 128 : 256 - i] = i == 0 ? 0.0f : neg;
       }
@@ -187,7 +190,7 @@ __global__ void __launch_bounds__(256) gelu_kernel(const int8_t* __restrict__ X,
   }
 }
 
-// GELU forward / backward for B = 32 and 64 with one quantization block per WAVE: the wave builds the block's
+// GELU forward / backward for B = 64 (tensors that the last-level cache holds) with one quantization block per WAVE: the wave builds the block's
 // table, looks its B x B codes up, takes the block max-abs with a wave reduction and stores -- no workgroup
 // barrier and no LDS exchange between waves, so the four waves of a workgroup (four neighbouring block columns)
 // run independently and one wave's table build overlaps its neighbours' loads and stores.  Lane = (row l / CPR,
@@ -223,19 +226,9 @@ __global__ void __launch_bounds__(256) gelu_wave_kernel(const int8_t* __restrict
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
     const int i = lane + 64 * h;
-    const float a = (float)i * sx;
-    const TailEval te = normal_tail(a);
     float pos, neg;
-    if (BWD) {
-      const float slope = a * 0.39894228040143268f;
-      pos = __builtin_fmaf(slope, te.ez, 1.0f - te.q);
-      neg = __builtin_fmaf(-slope, te.ez, te.q);
-    } else {
-      const float aq = a * te.q;
-      pos = a - aq;
-      neg = 0.0f - aq;
-    }
-    tab[i] = (BWD && i == 0) ? 0.5f : pos;  // GELU'(0) = 1/2 exactly, see gelu_kernel
+    gelu_table_entries<BWD>((float)i * sx, pos, neg);
+    tab[i] = (BWD && i == 0) ? 0.5f : pos;  // GELU'(0) = 1/2 exactly, see gelu_build_table
     tab[i == 0 ? 128 : 256 - i] = i == 0 ? 0.0f : neg;
   }
   // The table is written and read by this wave only; LDS serves a wave's accesses in program order, and the
@@ -401,62 +394,6 @@ __global__ void __launch_bounds__(256) dropout_kernel(const int8_t* __restrict__
 }
 
 // ------------------------------------------------------------------------------------------------
-// One table of GELU (or its derivative) at the 255 values code * sx of a block, indexed by the code byte taken as
-// unsigned: lane l evaluates codes l and l + 64 and, by symmetry, -l and -(l + 64).  Both functions are written in
-// terms of the upper tail Q(a) = Phi(-a), a >= 0 (App. A):
-//   GELU(x) = x Phi(x):  f(a) = a - a Q(a),  f(-a) = -a Q(a);
-//   GELU'(x) = Phi(x) + x phi(x):  f(a) = 1 - Q(a) + a phi(a),  f(-a) = Q(a) - a phi(a),  phi(a) = exp(-a^2/2) / sqrt(2 pi).
-//   Q(a) = t P(t) exp(-a^2/2),  t = 1 / (1 + a / sqrt(8)),  P of degree 8 fitted by weighted least squares on Chebyshev
-//   nodes to erfcx(a / sqrt 2) / (2 t) for 0 <= a <= 13.4 (relative error 5e-8; evaluated in FP32: 4e-7).
-// exp(-a^2/2) = 2^H (1 + r ln 2) with H = fl(-a^2 log2(e)/2) and r the exact remainder (product residuals by FMA),
-// so that the FP32 rounding of an exponent of size a^2 does not cost log2(a^2) bits: Q keeps a relative error of
-// about 1e-6 into the far tail, where a block that lies entirely there takes its scale from.
-template <bool BWD>
-__device__ __forceinline__ void gelu_table_entries(float a, float& pos, float& neg) {
-  const float ac = fminf(a, 40.0f);                       // Q(40) = 0 in FP32; keeps a^2 finite
-  const float t = __builtin_amdgcn_rcpf(__builtin_fmaf(ac, 0.35355339059327373f, 1.0f));
-  float p = -2.9970746985e-02f;
-  p = __builtin_fmaf(p, t, 1.4432375881e-01f);
-  p = __builtin_fmaf(p, t, -2.4760739076e-01f);
-  p = __builtin_fmaf(p, t, 1.4335782902e-01f);
-  p = __builtin_fmaf(p, t, -1.6097390692e-02f);
-  p = __builtin_fmaf(p, t, 1.0243339323e-01f);
-  p = __builtin_fmaf(p, t, 1.2129997806e-01f);
-  p = __builtin_fmaf(p, t, 1.4121892641e-01f);
-  p = __builtin_fmaf(p, t, 1.4104161820e-01f);
-  const float K = -0.72134752044448170f;                  // -log2(e) / 2
-  const float aa = ac * ac;
-  const float lo = __builtin_fmaf(ac, ac, -aa);           // a^2 = aa + lo exactly
-  const float H = aa * K;
-  const float r = __builtin_fmaf(lo, K, __builtin_fmaf(aa, K, -H));
-  const float ez = __builtin_amdgcn_exp2f(H) * __builtin_fmaf(r, 0.6931471805599453f, 1.0f);   // exp(-a^2/2)
-  const float q = (t * p) * ez;
-  if (BWD) {
-    const float s = (a * 0.39894228040143268f) * ez;      // a phi(a)
-    pos = (1.0f - q) + s;
-    neg = q - s;
-  } else {
-    const float aq = a * q;
-    pos = a - aq;
-    neg = 0.0f - aq;
-  }
-}
-
-template <bool BWD>
-__device__ __forceinline__ void gelu_build_table(float* tab, float sx, int lane) {
-#pragma unroll
-  for (int h = 0; h < 2; ++h) {
-    const int i = lane + 64 * h;
-    float pos, neg;
-    gelu_table_entries<BWD>((float)i * sx, pos, neg);
-    // code 0: GELU(0) = 0 comes out exactly; GELU'(0) = 1/2 is set, because the fit is only good to 4e-7 there and a
-    // derivative of 0.49999997 would push every halved gradient code off its rounding tie.  Entry 128 (code -128,
-    // which no quantizer output holds) is 0.
-    tab[i] = (BWD && i == 0) ? 0.5f : pos;
-    tab[i == 0 ? 128 : 256 - i] = i == 0 ? 0.0f : neg;
-  }
-}
-
 template <bool BWD>
 __global__ void __launch_bounds__(64 * kStripWaves) gelu_strip32_kernel(const int8_t* __restrict__ X, const float* __restrict__ SX,
                                                           const int8_t* __restrict__ G, const float* __restrict__ SG,

@@ -13,10 +13,10 @@
 namespace jf {
 
 // ------------------------------------------------------------------------------------------------
-// LayerNorm.  One workgroup of four waves owns B rows and all C columns; wave w owns rows
-// [w*B/4, (w+1)*B/4).  Lane l of a wave owns the 16-byte chunks l, l+64, ... of each of its rows, so a
-// row is read as contiguous 1 KB runs and per-column quantities (gamma, beta, column sums) stay in
-// registers while the wave walks down its rows.  NIT = ceil(C / 1024) chunks per lane and row.
+// Block sizes 64 and 128: one workgroup owns B rows and all C columns (C <= 4096), each wave a few of the rows.
+// Lane l of a wave owns the 16-byte chunks l, l+64, ... of each of its rows, so a row is read as contiguous 1 KB
+// runs and per-column quantities (gamma, beta, column sums) stay in registers while the wave walks down its
+// rows.  NIT = ceil(C / 1024) chunks per lane and row.
 
 // exact sums of the 16 codes of a chunk and of their squares
 __device__ __forceinline__ void chunk_moments(const uint4& p, int& s1, int& s2) {
@@ -630,8 +630,8 @@ struct RowStrips32 {
   __device__ __forceinline__ int64_t block_index(int bi) const { return (int64_t)bi * lc + col / 32; }
 };
 
-// Row statistics of LayerNorm from the codes (App. A: "mean and sum of squares", here of the INT8 input itself), for
-// rows of any width: the workgroup's waves share the strips of its 32 rows (wave w takes strips w, w + waves, ...).
+// Row statistics of LayerNorm from the codes (the per-row mean and sum of squares of App. A, here taken of the INT8 input
+// itself), for rows of any width: the workgroup's waves share the strips of its 32 rows (wave w takes strips w, w + waves, ...).
 // Per 16-code chunk the sum and the sum of squares of the codes are exact integers (v_dot4); times the block scale,
 // in double, they are the chunk's share of the row's sum and sum of squares.  The shares are added over a lane's
 // strips, over the 8 chunk lanes of a row (three DPP steps) and over the waves through LDS, in a fixed order.  The
@@ -696,8 +696,8 @@ __global__ void __launch_bounds__(1024) layernorm_row_stats_strips32_kernel(cons
 // compute unit with a single workgroup and nothing to overlap its memory latency with.)
 //
 // First kernel: the workgroup of strip waves described above walks over the row blocks blockIdx.x, blockIdx.x +
-// gridDim.x, ... (four waves per SIMD: another workgroup's loads run beside this one's arithmetic).  The row sums go over the chunk lanes, then over the
-// strips through LDS (two copies used by alternate row blocks: one barrier per block); the running column sums of
+// gridDim.x, ... (four waves per SIMD: another workgroup's loads run beside this one's arithmetic).  The row sums go
+// over the chunk lanes, then over the strips through LDS (two copies used by alternate row blocks: one barrier per block); the running column sums of
 // g xhat and g stay in registers over all row blocks -- a lane always holds the same 16 columns -- and are added
 // over the 8 row lanes of the wave at the end (every wave owns its own 128 columns of the partial row).  All orders
 // are fixed: results are bit-stable from run to run.
@@ -788,8 +788,9 @@ __global__ void __launch_bounds__(64 * WMAX) __attribute__((amdgpu_waves_per_eu(
 }
 
 // Second kernel: dx on 32 x 128 strips, one wave each, from the row means q1 = mean_C(ghat), q2 = mean_C(ghat xhat)
-// that the first kernel left (one share per range of 2048 columns): dx = ug a_c + ux b + d with per-row b = -rstd q2 sx rstd, d and per-column
-// a_c = rstd sg gamma_c (u = code + 128), then Eq. 1.  Rows may be of any width.
+// that the first kernel left (one share per range of 2048 columns): dx = ug a_c + ux b + d with per-row
+// b = -rstd q2 sx rstd and d, and per-column a_c = rstd sg gamma_c (u = code + 128), then Eq. 1.  Rows may be of any
+// width.
 __global__ void __launch_bounds__(64 * kStripWaves) layernorm_bwd_apply_strip32_kernel(
     const int8_t* __restrict__ G, const float* __restrict__ SG, const int8_t* __restrict__ X, const float* __restrict__ SX,
     const float* __restrict__ gamma, const float* __restrict__ mean_in, const float* __restrict__ rstd_in,
@@ -875,7 +876,7 @@ __global__ void __launch_bounds__(256) row_stats_from_partials_kernel(const floa
   }
 }
 
-// LayerNorm at block size 32 from given row statistics (App. A: the operator "directly accesses" mean and rstd):
+// LayerNorm at block size 32 from given row statistics (App. A: the operator is handed the row mean and rstd):
 // y = (x - mean) rstd gamma + beta on 32 x 128 strips, one wave each, like the other element-wise operators --
 // no workgroup needs a whole row, so rows may be of any width.
 __global__ void __launch_bounds__(64 * kStripWaves) layernorm_apply_strip32_kernel(const int8_t* __restrict__ X, const float* __restrict__ SX,

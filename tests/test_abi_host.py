@@ -145,3 +145,19 @@ def test_static_scratch_entry_point_rejects_what_does_not_fit():
     assert call(65 * 64, 4096, block=64) == 5              # JF_ERR_WORKSPACE
     assert binding.jf_workspace_bytes(binding.JF_OP_LAYERNORM_BWD, 1 << 20, 768, 0, 32) > scratch      # 8 bytes per row
     assert call(1 << 20, 768) == 5
+
+
+def test_linear_bwd_validates_like_dgrad_and_wgrad():
+    lib = binding.load_library()
+    N, C, D = 64, 64, 64
+
+    def call(dY=FAKE, X=FAKE, dX=FAKE, SdX=FAKE, dW=FAKE, SdW=FAKE, dWf=None, N=N, block=32):
+        return lib.jf_linear_bwd(dY, FAKE, FAKE, FAKE, X, FAKE, N, C, D, block, dX, SdX, None, dW, SdW, dWf, None, 0, None)
+    assert call(dY=None) == 1                              # JF_ERR_NULL
+    assert call(X=None) == 1
+    assert call(dX=None) == 1                              # the input gradient's INT8 output is required ...
+    assert call(dW=None, SdW=None) == 1                    # ... and the weight gradient needs at least one output
+    assert call(dW=FAKE, SdW=None) == 1                    # codes and scales come together
+    assert call(N=48) == 2                                 # JF_ERR_SHAPE
+    assert call(block=48) == 3                             # JF_ERR_BLOCK
+    assert call(X=ODD) == 4                                # JF_ERR_ALIGN

@@ -16,15 +16,15 @@
  * Readings of points the paper leaves open (each also listed in the design
  * notes of the repository):
  *   - scale  s = max|x| / 127 over the block, computed as one FP32 division
- *     (Sec. 4 says the scale "corresponds to" the block maximum, Eq. 1 divides
- *     by it; 127 makes the largest element map to +-127);
+ *     (Sec. 4 ties the scale to the block maximum without giving a formula, Eq. 1
+ *     divides by it; 127 makes the largest element map to +-127);
  *   - the round operator of Eq. 1 is round-half-to-even of the exact quotient,
  *     evaluated here in double (x and s are FP32 numbers);
  *   - an all-zero block gets s = 0 and all codes 0;
  *   - the FP32 accumulator of Sec. 5.3 / Alg. 1 is updated, per K-block k in
  *     ascending order, as  acc = fma(fl32(s_X * s_W), (float)Y_int32, acc);
  *     the same sum in double is returned beside it as the "exact" value;
- *   - the output quantizer of Alg. 1 (line "quantize the output") is Eq. 1
+ *   - the output quantizer of Alg. 1 (its last step before the store) is Eq. 1
  *     applied to that FP32 accumulator;
  *   - GELU uses the exact-erf form of App. A, LayerNorm uses biased variance,
  *     statistics of the dequantized INT8 input, and the standard gradient.

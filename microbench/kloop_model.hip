@@ -106,6 +106,9 @@ int main() {
   run<1, 4, 2, 2, 3, true, 2>("B=32  64x64, 4 waves, KC 64", src, scales);
   run<1, 4, 4, 4, 3, true, 2>("B=32  64x64, 4 waves, KC 128", src, scales);
   run<1, 4, 2, 2, 4, true, 2>("B=32  64x64, 4 waves, KC 64", src, scales);
+  // a 64x64 tile whose four waves split K (each wave 2x2 sub-blocks of one K step per stage of 128 K bytes: 4 loads,
+  // 4 units, one fragment read per unit); not built -- it would sum every output element in four chains
+  run<1, 4, 4, 4, 3, true, 1>("B=32  64x64, 4 waves splitting K, KC 128", src, scales);
   // block 64: same tile, a stage holds one quantization block: 4 units of 2 MFMAs
   run<2, 4, 4, 4, 3, false>("B=64  128x128, 4 waves", src, scales);
   run<2, 4, 4, 4, 3, true>("B=64  128x128, 4 waves", src, scales);

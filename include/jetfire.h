@@ -167,9 +167,7 @@ int32_t jf_gelu_q_bwd(const int8_t* dY, const float* SdY, const int8_t* X, const
  * are those of the dequantized input; y = (x - mean) * rstd * gamma + beta.
  * gamma, beta: FP32 [C] (Sec. 7.1 keeps them in floating point).
  * Outputs: Y codes + SY, and mean[N], rstd[N] (FP32, saved for backward).
- * Rows may be of any width at block 32; at block 64 and 128, C <= 4096
- * (JF_ERR_SHAPE otherwise).  The same holds for the two LayerNorm entry
- * points below.
+ * Rows may be of any width (no workgroup holds a whole row).
  */
 int32_t jf_layernorm_q(const int8_t* X, const float* SX, const float* gamma, const float* beta, float eps, int64_t N,
                        int64_t C, int32_t block, int8_t* Y, float* SY, float* mean, float* rstd, void* stream);
@@ -213,7 +211,7 @@ int32_t jf_dropout_q(const int8_t* X, const float* SX, const uint8_t* mask_bits,
  *   dX = rstd (ghat - mean_C(ghat) - xhat mean_C(ghat xhat)),
  *   dgamma = sum_N dY xhat,  dbeta = sum_N dY   (FP32 [C], fixed summation order).
  * Needs jf_workspace_bytes(JF_OP_LAYERNORM_BWD, N, C, 0, block) bytes of ws
- * (partial rows of dgamma | dbeta; at block 32 also the two row means of every
+ * (at most 512 partial rows of dgamma | dbeta, and the two row means of every
  * row, which the pass hands from its first kernel to its second).
  */
 int32_t jf_layernorm_q_bwd(const int8_t* dY, const float* SdY, const int8_t* X, const float* SX, const float* gamma,
@@ -229,9 +227,9 @@ int32_t jf_layernorm_q_bwd(const int8_t* dY, const float* SdY, const int8_t* X, 
  * inside the library (one copy per GPU, held until the process ends).  The call
  * allocates and frees nothing.  Problems whose
  * jf_workspace_bytes(JF_OP_LAYERNORM_BWD, N, C, 0, block) exceeds
- * JF_STATIC_SCRATCH_BYTES are rejected with JF_ERR_WORKSPACE (at block 32 and
- * C = 768 that admits 655360 rows: 6 KiB per partial row, at most 512 of them,
- * plus 8 bytes per row).
+ * JF_STATIC_SCRATCH_BYTES are rejected with JF_ERR_WORKSPACE (at C = 768 that
+ * admits 655360 rows: 6 KiB per partial row, at most 512 of them, plus 8 bytes
+ * per row).
  * All calls on one GPU share that GPU's array: calls that overlap in time on
  * one GPU (different streams or threads) race; calls on one stream do not.
  * The first call on a device looks the array's address up

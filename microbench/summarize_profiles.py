@@ -131,8 +131,8 @@ def bench_hbm_traffic():
             "The excess on the read side is re-reading by the eight XCDs: each XCD's L2 pulls its own copy of the operand band it",
             "works on from the Infinity Cache / HBM (FETCH_SIZE counts L2 misses, many of which hit the Infinity Cache).", ""]
     others = [("quantize (mean over X, W, dH)", "quantize_kernel"), ("gelu fwd", "gelu_strip32_kernel<false"), ("gelu bwd", "gelu_strip32_kernel<true"),
-              ("layernorm fwd: row statistics", "layernorm_row_stats_strips32_kernel"), ("layernorm fwd: normalise (strips)", "layernorm_apply_strip32_kernel"),
-              ("layernorm bwd: sums", "layernorm_bwd_sums_strips32_kernel"), ("layernorm bwd: dx (strips)", "layernorm_bwd_apply_strip32_kernel"),
+              ("layernorm fwd: row statistics", "layernorm_row_stats_kernel"), ("layernorm fwd: normalise (strips)", "layernorm_apply_strip32_kernel"),
+              ("layernorm bwd: sums", "layernorm_bwd_sums_kernel"), ("layernorm bwd: dx (strips)", "layernorm_bwd_apply_strip32_kernel"),
               ("colsum (dgamma, dbeta)", "colsum_kernel")]
     for name, key in others:
         f, w = avg(fe, lambda k: key in k) * sf, avg(wr, lambda k: key in k) * sw

@@ -26,7 +26,7 @@ extern "C" size_t jf_workspace_bytes(int32_t op, int64_t N, int64_t C, int64_t D
   if (!jf::valid_block(block) || N <= 0 || C <= 0) return 0;
   switch (op) {
     case JF_OP_LAYERNORM_BWD:
-      return jf::ln_bwd_workspace_bytes(N, C, block);
+      return jf::ln_bwd_workspace_bytes(N, C);
     default:
       return 0;
   }

@@ -31,19 +31,13 @@ inline bool aligned4(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 3
 inline bool valid_block(int32_t b) { return b == 32 || b == 64 || b == 128; }
 // Dimensions are kept below 2^24 so that every index fits an int32 after
 // division by the block size and element offsets fit 48 bits.
-// Rows of dgamma | dbeta partial sums that the LayerNorm backward kernels leave in the workspace.  A workgroup walks
-// over the row blocks it owns and leaves one row (at most 512 workgroups); at block sizes 64 and 128, rows wider
-// than 2048 columns use one workgroup per row block, which leaves four.
-inline int64_t ln_bwd_partial_rows(int64_t N, int64_t C, int32_t block) {
-  if (C > 2048 && block != 32) return (N / block) * 4;
-  return N / block < 512 ? N / block : 512;
-}
-// Workspace of LayerNorm backward: the partial rows (dgamma | dbeta, 2 C floats each), and for block size 32, where
-// the pass runs as two kernels, the two row means of every row behind them (one pair per range of 2048 columns).
-inline size_t ln_bwd_workspace_bytes(int64_t N, int64_t C, int32_t block) {
-  size_t bytes = (size_t)ln_bwd_partial_rows(N, C, block) * 2 * (size_t)C * sizeof(float);
-  if (block == 32) bytes += (size_t)N * 2 * sizeof(float) * (size_t)((C + 2047) / 2048);
-  return bytes;
+// Rows of dgamma | dbeta partial sums that the first kernel of LayerNorm backward leaves in the workspace: one per
+// workgroup, which walks over the groups of 32 rows it owns (at most 512 workgroups).
+inline int64_t ln_bwd_partial_rows(int64_t N) { return N / 32 < 512 ? N / 32 : 512; }
+// Workspace of LayerNorm backward: the partial rows (dgamma | dbeta, 2 C floats each), and behind them the two row means
+// of every row that the first kernel hands to the second (one pair per range of 2048 columns).
+inline size_t ln_bwd_workspace_bytes(int64_t N, int64_t C) {
+  return (size_t)ln_bwd_partial_rows(N) * 2 * (size_t)C * sizeof(float) + (size_t)N * 2 * sizeof(float) * (size_t)((C + 2047) / 2048);
 }
 inline bool valid_dim(int64_t d, int32_t block) { return d > 0 && d <= (int64_t(1) << 24) && d % block == 0; }
 // A tensor holds at most 2^40 elements (far beyond any device memory): keeps every workgroup count inside 32 bits.

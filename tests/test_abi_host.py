@@ -31,7 +31,8 @@ def test_error_strings_and_workspace():
     for code in range(1, 8):
         assert lib.jf_error_string(code).startswith(b"JF_ERR_")
     assert binding.jf_workspace_bytes(binding.JF_OP_LAYERNORM_BWD, 4096, 768, 0, 32) == 128 * 2 * 768 * 4 + 4096 * 2 * 4
-    assert binding.jf_workspace_bytes(binding.JF_OP_LAYERNORM_BWD, 4096, 768, 0, 64) == 64 * 2 * 768 * 4
+    assert binding.jf_workspace_bytes(binding.JF_OP_LAYERNORM_BWD, 4096, 768, 0, 64) == 128 * 2 * 768 * 4 + 4096 * 2 * 4
+    assert binding.jf_workspace_bytes(binding.JF_OP_LAYERNORM_BWD, 1 << 20, 3072, 0, 128) == 512 * 2 * 3072 * 4 + (1 << 20) * 2 * 4 * 2
     assert binding.jf_workspace_bytes(binding.JF_OP_LINEAR_FWD, 4096, 768, 3072, 32) == 0
     assert binding.jf_workspace_bytes(binding.JF_OP_LAYERNORM_BWD, 4096, 768, 0, 48) == 0
 
@@ -136,13 +137,11 @@ def test_static_scratch_entry_point_rejects_what_does_not_fit():
                                                                        FAKE, FAKE, FAKE, FAKE, None)
     assert call(64, 64, dY=None) == 1                      # JF_ERR_NULL
     assert call(48, 64) == 2                               # JF_ERR_SHAPE
-    assert call(64, 8192, block=64) == 2                   # rows wider than 4096 columns (any width only at block 32)
     assert call(64, 64, block=48) == 3                     # JF_ERR_BLOCK
     assert call(64, 64, dY=ODD) == 4                       # JF_ERR_ALIGN
     scratch = 8 << 20
-    assert binding.jf_workspace_bytes(binding.JF_OP_LAYERNORM_BWD, 1 << 20, 2048, 0, 64) == scratch     # the largest that fits
-    assert binding.jf_workspace_bytes(binding.JF_OP_LAYERNORM_BWD, 65 * 64, 4096, 0, 64) > scratch
-    assert call(65 * 64, 4096, block=64) == 5              # JF_ERR_WORKSPACE
+    assert binding.jf_workspace_bytes(binding.JF_OP_LAYERNORM_BWD, 16384, 4096, 0, 64) > scratch       # 512 partial rows of 32 KiB
+    assert call(16384, 4096, block=64) == 5                # JF_ERR_WORKSPACE
     assert binding.jf_workspace_bytes(binding.JF_OP_LAYERNORM_BWD, 1 << 20, 768, 0, 32) > scratch      # 8 bytes per row
     assert call(1 << 20, 768) == 5
 

@@ -364,12 +364,12 @@ def test_layernorm_fwd_bwd(block, N, C):
     assert torch.equal(dgam, dgam2) and torch.equal(dbet, dbet2) and torch.equal(dX, dX2)
 
 
-@pytest.mark.parametrize("N,C", [(64, 8192), (96, 5152), (128, 3072)])
-def test_layernorm_wide_rows(N, C):
-    """Block size 32 works on strips after a pass that only leaves sums, so rows may be wider than a workgroup could
-    hold (hidden 8192 is the widest LayerNorm the paper's speed comparison quotes); 5152 leaves a ragged last strip
-    and a last column range that uses a part of its waves."""
-    block = 32
+@pytest.mark.parametrize("block,N,C", [(32, 64, 8192), (32, 96, 5152), (32, 128, 3072), (64, 128, 8192), (64, 192, 4800),
+                                       (128, 256, 8192), (128, 128, 5248)])
+def test_layernorm_wide_rows(block, N, C):
+    """LayerNorm works on tiles after a pass that only leaves sums, so rows may be wider than a workgroup could hold
+    (hidden 8192 is the widest LayerNorm the paper's speed comparison quotes); 5152 / 4800 / 5248 leave a ragged last
+    strip and a last column range that uses a part of its waves."""
     say(f"layernorm wide rows {N}x{C}")
     x, gamma, beta, gr = workloads.layernorm_case(6500 + C, N, C)
     (X, SX), (G, SG) = oracle.quantize_block(x, block), oracle.quantize_block(gr, block)

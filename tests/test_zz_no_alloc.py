@@ -52,7 +52,7 @@ def test_static_scratch_matches_workspace_entry_point(block, first, second):
 
 
 def test_static_scratch_rejects_what_does_not_fit():
-    N, C, block = 65 * 64, 4096, 64                          # 8.1 MiB of partial rows
+    N, C, block = 16384, 4096, 64                            # 512 partial rows of 32 KiB: 16 MiB
     assert jf.jf_workspace_bytes(7, N, C, 0, block) > (8 << 20)
     args = tuple(torch.zeros(s, dtype=d, device=DEV) for s, d in (((N, C), torch.int8), ((N // block, C // block), torch.float32),
                                                                 ((N, C), torch.int8), ((N // block, C // block), torch.float32),

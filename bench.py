@@ -494,7 +494,7 @@ def main():
     }
     # the residual / dropout operators of the transformer block on the same 4096 x 3072 tensor
     mask_bits = torch.randint(0, 256, (N, D // 8), dtype=torch.uint8, device=dev)
-    rm, rq = torch.empty((N, D // B), dtype=torch.float32, device=dev), torch.empty((N, D // B), dtype=torch.float32, device=dev)
+    rm, rq = torch.empty((D // B, N), dtype=torch.float32, device=dev), torch.empty((D // B, N), dtype=torch.float32, device=dev)
     ops["add"] = (lambda: jf.jf_add_q(Y, SY, H, SH, B, out=(dY, SdY)), N * D * (3 + 3 * sb))
     ops["add_with_row_partials"] = (lambda: jf.jf_add_q(Y, SY, H, SH, B, want_partials=True, out=(dY, SdY, rm, rq)),
                                     N * D * (3 + 3 * sb + 8.0 / B))
@@ -503,7 +503,7 @@ def main():
     # partials of the 4096 x 768 input written by an Add of it with a zero tensor
     zq, zs = torch.zeros_like(Xq), torch.zeros_like(SX)
     xr, sxr = torch.empty_like(Xq), torch.empty_like(SX)
-    pm, pq = (torch.empty((N, C // B), dtype=torch.float32, device=dev) for _ in range(2))
+    pm, pq = (torch.empty((C // B, N), dtype=torch.float32, device=dev) for _ in range(2))
     jf.jf_add_q(Xq, SX, zq, zs, B, want_partials=True, out=(xr, sxr, pm, pq))
     ops["layernorm_fwd_from_row_partials"] = (
         lambda: jf.jf_layernorm_q_partials(xr, sxr, pm, pq, gamma, beta, 1e-5, B, out=(Xn, SXn, mean, rstd)),
@@ -564,7 +564,7 @@ def main():
         }
         # the paper's own LayerNorm design: statistics from the row partials of the preceding Add (written here by an Add
         # of the tensor with zeros)
-        pml, pql = (torch.empty((NL, C // B), dtype=torch.float32, device=dev) for _ in range(2))
+        pml, pql = (torch.empty((C // B, NL), dtype=torch.float32, device=dev) for _ in range(2))
         zl, szl = torch.zeros_like(xl), torch.zeros_like(sxl)
         big["add_with_row_partials"] = (lambda: jf.jf_add_q(xl, sxl, zl, szl, B, want_partials=True, out=(yl, syl, pml, pql)),
                                         NL * C * (3 + 3 * sb + 8.0 / B))

@@ -175,10 +175,10 @@ int32_t jf_layernorm_q(const int8_t* X, const float* SX, const float* gamma, con
 /*
  * INT8 LayerNorm that takes its row statistics from the partials of the
  * preceding Add (App. A, LayerNorm paragraph) instead of a pass over X:
- *   mean_i = (1/L_C) sum_j row_mean[i][j],  E[x^2]_i = (1/C) sum_j row_sumsq[i][j],
+ *   mean_i = (1/L_C) sum_j row_mean[j][i],  E[x^2]_i = (1/C) sum_j row_sumsq[j][i],
  *   var_i = max(E[x^2]_i - mean_i^2, 0),  rstd_i = 1/sqrt(var_i + eps),
  * then y = (x - mean) * rstd * gamma + beta on the dequantized X as above.
- * row_mean, row_sumsq: FP32 N x (C/block), row-major, as written by jf_add_q.
+ * row_mean, row_sumsq: FP32 (C/block) x N, as written by jf_add_q.
  */
 int32_t jf_layernorm_q_partials(const int8_t* X, const float* SX, const float* row_mean, const float* row_sumsq,
                                 const float* gamma, const float* beta, float eps, int64_t N, int64_t C, int32_t block,
@@ -187,10 +187,13 @@ int32_t jf_layernorm_q_partials(const int8_t* X, const float* SX, const float* r
 /*
  * INT8 Add (App. A): Y = Q(X1 + X2) on the dequantized operands, the residual
  * connection forward and dx = df(y) + dy backward.  X1, X2: N x C codes with
- * grids S1, S2; Y, SY out.  row_mean / row_sumsq (both NULL or both non-NULL,
- * FP32 N x (C/block)) receive, for every row and block column, the mean and
- * the sum of squares of the FP32 sum over the block's columns -- the row
- * partials that App. A attaches to this operator for the LayerNorm after it.
+ * grids S1, S2; Y, SY out.  row_mean / row_sumsq (both NULL or both non-NULL)
+ * receive, for every row and block column, the mean and the sum of squares of
+ * the FP32 sum over the block's columns -- the row partials that App. A
+ * attaches to this operator for the LayerNorm after it.  They are FP32
+ * matrices of (C/block) x N, i.e. stored block column by block column (one
+ * row of N values per block column), so that both the writer and the reader
+ * touch whole memory lines.
  */
 int32_t jf_add_q(const int8_t* X1, const float* S1, const int8_t* X2, const float* S2, int64_t N, int64_t C,
                  int32_t block, int8_t* Y, float* SY, float* row_mean, float* row_sumsq, void* stream);

@@ -239,8 +239,8 @@ def jf_layernorm_q_partials(X, SX, row_mean, row_sumsq, gamma, beta, eps=1e-5, b
     _dev(X, torch.int8, 2), _dev(SX, torch.float32, 2), _dev(gamma, torch.float32, 1), _dev(beta, torch.float32, 1)
     _dev(row_mean, torch.float32, 2), _dev(row_sumsq, torch.float32, 2)
     N, C = X.shape
-    if tuple(row_mean.shape) != (N, C // block) or tuple(row_sumsq.shape) != (N, C // block):
-        raise JetfireError(2, "row partials must be (N, C / block)")
+    if tuple(row_mean.shape) != (C // block, N) or tuple(row_sumsq.shape) != (C // block, N):
+        raise JetfireError(2, "row partials must be (C / block, N), as jf_add_q writes them")
     if out is not None:
         Y, SY, mean, rstd = out
     else:
@@ -266,7 +266,8 @@ def jf_dropout_q(X, SX, mask_bits, p, block=32, out=None):
 
 
 def jf_add_q(X1, S1, X2, S2, block=32, want_partials=False, out=None):
-    """Y = Q(X1 + X2); with want_partials also the (N, C/block) row partials (mean, sum of squares) of the sum."""
+    """Y = Q(X1 + X2); with want_partials also the row partials (mean, sum of squares) of the sum, stored block column by
+    block column: two (C/block, N) tensors."""
     _dev(X1, torch.int8, 2), _dev(S1, torch.float32, 2), _dev(X2, torch.int8, 2), _dev(S2, torch.float32, 2)
     N, C = X1.shape
     if X2.shape != X1.shape:
@@ -279,8 +280,8 @@ def jf_add_q(X1, S1, X2, S2, block=32, want_partials=False, out=None):
     else:
         Y, SY = torch.empty_like(X1), torch.empty_like(S1)
         if want_partials:
-            rm = torch.empty((N, C // block), dtype=torch.float32, device=X1.device)
-            rq = torch.empty((N, C // block), dtype=torch.float32, device=X1.device)
+            rm = torch.empty((C // block, N), dtype=torch.float32, device=X1.device)
+            rq = torch.empty((C // block, N), dtype=torch.float32, device=X1.device)
     _check(load_library().jf_add_q(_ptr(X1), _ptr(S1), _ptr(X2), _ptr(S2), N, C, block, _ptr(Y), _ptr(SY), _ptr(rm),
                                    _ptr(rq), _stream()))
     return (Y, SY, rm, rq) if want_partials else (Y, SY)

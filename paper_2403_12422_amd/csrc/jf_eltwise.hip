@@ -279,7 +279,7 @@ __global__ void __launch_bounds__(256) gelu_wave_kernel(const int8_t* __restrict
 // ------------------------------------------------------------------------------------------------
 // Add (App. A): y = x1 + x2 on the dequantized operands, re-quantized per block (Alg. 2), and optionally
 // the row partials that App. A's LayerNorm paragraph attaches to this operator: for every row and block
-// column, the mean and the sum of squares of y over the block's B columns.  Same tiling as GELU.
+// column, the mean and the sum of squares of y over the block's B columns (stored block-column-major).  Same tiling as GELU.
 template <int B>
 __global__ void __launch_bounds__(256) add_kernel(const int8_t* __restrict__ X1, const float* __restrict__ S1,
                                                    const int8_t* __restrict__ X2, const float* __restrict__ S2, int rows,
@@ -320,8 +320,8 @@ __global__ void __launch_bounds__(256) add_kernel(const int8_t* __restrict__ X1,
         ps = wave_group_sum<CH>(ps);
         pq = wave_group_sum<CH>(pq);
         if ((ch & CH) == 0) {
-          row_mean[(int64_t)row * lc + col / B] = ps * (1.0f / (float)B);
-          row_sumsq[(int64_t)row * lc + col / B] = pq;
+          row_mean[(int64_t)(col / B) * rows + row] = ps * (1.0f / (float)B);   // block-column-major, see jf_add_q
+          row_sumsq[(int64_t)(col / B) * rows + row] = pq;
         }
       }
     }
@@ -495,7 +495,8 @@ __global__ void __launch_bounds__(64 * kStripWaves) add_strip32_kernel(const int
       ps = wave_group_sum<1>(ps);
       pq = wave_group_sum<1>(pq);
       if (t.ok && (t.ch & 1) == 0) {
-        const int64_t o = (int64_t)(t.bi * 32 + t.rsub + 8 * p) * t.lc + t.col / 32;
+        // block-column-major: the 32 rows of the strip are one 128-byte line per block column
+        const int64_t o = (int64_t)(t.col / 32) * rows + (t.bi * 32 + t.rsub + 8 * p);
         row_mean[o] = ps * (1.0f / 32.0f);
         row_sumsq[o] = pq;
       }

@@ -272,34 +272,39 @@ __global__ void __launch_bounds__(64 * kStripWaves) layernorm_bwd_apply_strip32_
 }
 
 // Row statistics of LayerNorm from the row partials that the preceding Add wrote (App. A, LayerNorm paragraph):
-//   mean_i = (1 / L_C) sum_j row_mean[i][j],  var_i = max((1 / C) sum_j row_sumsq[i][j] - mean_i^2, 0),
-// summed in double in a fixed order; rstd as the hardware reciprocal square root plus one Newton step.  A group of
-// 8 lanes owns a row: the lanes read the row's partials as consecutive floats (a wave reads eight rows, which lie
-// back to back in memory) and add their shares with three butterfly steps.
-__global__ void __launch_bounds__(256) row_stats_from_partials_kernel(const float* __restrict__ row_mean,
-                                                                       const float* __restrict__ row_sumsq, float eps,
-                                                                       int rows, int lc, int cols,
-                                                                       float* __restrict__ mean_out, float* __restrict__ rstd_out) {
-  const int sub = threadIdx.x & 7;
-  const int row = min(blockIdx.x * 32 + (threadIdx.x >> 3), rows - 1);   // surplus groups repeat the last row
-  const float* pm = row_mean + (int64_t)row * lc;
-  const float* pq = row_sumsq + (int64_t)row * lc;
+//   mean_i = (1 / L_C) sum_j row_mean[j][i],  var_i = max((1 / C) sum_j row_sumsq[j][i] - mean_i^2, 0),
+// summed in double in a fixed order; rstd as the hardware reciprocal square root plus one Newton step.  The partials are
+// stored block-column-major ((C / B) x N): a workgroup owns 64 consecutive rows, lane = row, so every load of a wave is
+// 64 consecutive floats; its waves (4 to 16, about one per four block columns) take the block columns j = w, w + waves,
+// ... and their shares are added through LDS in wave order.
+__global__ void __launch_bounds__(1024) row_stats_from_partials_kernel(const float* __restrict__ row_mean,
+                                                                        const float* __restrict__ row_sumsq, float eps,
+                                                                        int rows, int lc, int cols,
+                                                                        float* __restrict__ mean_out, float* __restrict__ rstd_out) {
+  __shared__ double s_part[16][64][2];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, NW = blockDim.x >> 6;
+  const int row = min((int)blockIdx.x * 64 + lane, rows - 1);   // lanes past the last row repeat it and write nothing
   double s = 0.0, q = 0.0;
-  for (int j = sub; j < lc; j += 8) {
-    s += (double)pm[j];
-    q += (double)pq[j];
+  for (int j = wave; j < lc; j += NW) {
+    s += (double)row_mean[(int64_t)j * rows + row];
+    q += (double)row_sumsq[(int64_t)j * rows + row];
   }
-  s = wave_group_sum_f64<7>(s);
-  q = wave_group_sum_f64<7>(q);
+  s_part[wave][lane][0] = s;
+  s_part[wave][lane][1] = q;
+  __syncthreads();
+  if (wave != 0 || (int)blockIdx.x * 64 + lane >= rows) return;
+  s = q = 0.0;
+  for (int w = 0; w < NW; ++w) {
+    s += s_part[w][lane][0];
+    q += s_part[w][lane][1];
+  }
   const double mu = s / (double)lc;
   const float var = fmaxf((float)(q / (double)cols - mu * mu), 0.0f);
   const float ve = var + eps;
   float rs = __builtin_amdgcn_rsqf(ve);
   rs = rs * __builtin_fmaf(-0.5f * ve * rs, rs, 1.5f);
-  if (sub == 0) {
-    mean_out[row] = (float)mu;
-    rstd_out[row] = rs;
-  }
+  mean_out[row] = (float)mu;
+  rstd_out[row] = rs;
 }
 
 // LayerNorm at block size 32 from given row statistics (App. A: the operator is handed the row mean and rstd):
@@ -476,7 +481,8 @@ static int32_t layernorm_fwd(const int8_t* X, const float* SX, const float* row_
   if (!aligned16(gamma) || !aligned16(beta) || !aligned4(mean) || !aligned4(rstd)) return JF_ERR_ALIGN;
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   if (row_mean != nullptr) {
-    hipLaunchKernelGGL(row_stats_from_partials_kernel, dim3((unsigned)((N + 31) / 32)), dim3(256), 0, st, row_mean, row_sumsq,
+    const int waves = (int)std::min<int64_t>(16, std::max<int64_t>(4, C / block / 4));
+    hipLaunchKernelGGL(row_stats_from_partials_kernel, dim3((unsigned)((N + 63) / 64)), dim3(64 * waves), 0, st, row_mean, row_sumsq,
                        eps, (int)N, (int)(C / block), (int)C, mean, rstd);
   } else {
     const int waves = (int)std::min<int64_t>(16, (C + 127) / 128);

@@ -98,11 +98,11 @@ def test_config4_transformer_block_forward_backward():
     R1, SR1, rm, rq, f = oracle.add_q(X, SX, P, SP, B)
     got = jf.jf_add_q(*d(X, SX, P, SP), B, want_partials=True)
     eltwise("residual add 1", got, (R1, SR1, f))
-    np.testing.assert_allclose(host(got[2]), rm, rtol=0, atol=1e-5 * np.abs(f).max())
-    np.testing.assert_allclose(host(got[3]), rq, rtol=1e-5)
+    np.testing.assert_allclose(host(got[2]).T, rm, rtol=0, atol=1e-5 * np.abs(f).max())     # stored (C / block, N)
+    np.testing.assert_allclose(host(got[3]).T, rq, rtol=1e-5)
     mean2, rstd2 = oracle.row_stats_from_partials(rm, rq, H, eps, B)
     A2, SA2, f = oracle.layernorm_q_stats(R1, SR1, g2, b2, mean2, rstd2, B)
-    got = jf.jf_layernorm_q_partials(*d(R1, SR1, rm, rq, g2, b2), eps, B)
+    got = jf.jf_layernorm_q_partials(*d(R1, SR1, rm.T, rq.T, g2, b2), eps, B)
     eltwise("ln2 from partials", got, (A2, SA2, f))
     np.testing.assert_allclose(host(got[3]), rstd2, rtol=1e-5)
     H1, SH1 = linear("fc1", 0, A2, SA2, W1_, SW1)

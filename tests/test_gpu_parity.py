@@ -406,11 +406,12 @@ def test_add_and_layernorm_from_partials(block, N, C):
     assert torch.equal(Y, Yn) and torch.equal(SY, SYn)
     # partials are FP32 sums of B terms: tolerance relative to the sum of magnitudes
     absum = np.abs(of).reshape(N, C // block, block).sum(axis=2)
-    assert np.all(np.abs(host(rm).astype(np.float64) - orm) <= 1e-5 * absum / block + 1e-30)
-    assert np.all(np.abs(host(rq).astype(np.float64) - orq) <= 1e-5 * orq + 1e-30)
+    # (the library stores the partials block column by block column: (C / block, N))
+    assert np.all(np.abs(host(rm).T.astype(np.float64) - orm) <= 1e-5 * absum / block + 1e-30)
+    assert np.all(np.abs(host(rq).T.astype(np.float64) - orq) <= 1e-5 * orq + 1e-30)
     # LayerNorm from the ORACLE's partials, so that both sides start from identical inputs
     eps = 1e-5
-    Z, SZ, mean, rstd = jf.jf_layernorm_q_partials(dev(oY), dev(oSY), dev(orm), dev(orq), gd, bd, eps, block)
+    Z, SZ, mean, rstd = jf.jf_layernorm_q_partials(dev(oY), dev(oSY), dev(orm.T), dev(orq.T), gd, bd, eps, block)
     omean, orstd = oracle.row_stats_from_partials(orm, orq, C, eps, block)
     oZ, oSZ, oz = oracle.layernorm_q_stats(oY, oSY, gamma, beta, omean, orstd, block)
     np.testing.assert_allclose(host(mean), omean, rtol=0, atol=1e-5 * np.abs(of).max())
